@@ -1,0 +1,480 @@
+// Host side of the C boundary declared in include/lopt.h: argument validation, the planner that
+// turns a tensor list into the device tables the kernels walk, and the launch sequence of a step.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "lopt_internal.h"
+
+using namespace lopt;
+
+namespace {
+
+thread_local std::string g_last_error;
+
+inline uint32_t pad4(uint64_t x) { return (uint32_t)((x + 3) & ~(uint64_t)3); }
+inline uint64_t align64(uint64_t x) { return (x + 63) & ~(uint64_t)63; }
+
+int padded_hidden(int H) {
+  for (int hp : {4, 8, 16, 32})
+    if (H <= hp) return hp;
+  return 0;
+}
+
+size_t mlp_count(int d, int H) { return (size_t)d * H + H + (size_t)H * H + H + 2 * (size_t)H + 2; }
+
+bool config_ok(const lopt_config* c, std::string* why) {
+  auto bad = [&](const char* m) { if (why) *why = m; return false; };
+  if (!c) return bad("config is null");
+  if (c->struct_size != sizeof(lopt_config)) return bad("config.struct_size does not match sizeof(lopt_config)");
+  if (c->kind != LOPT_SMALL_FC && c->kind != LOPT_VELO) return bad("config.kind is not a lopt_kind");
+  if (c->hidden < 1 || c->hidden > 32) return bad("config.hidden must be in [1, 32]");
+  const float d[7] = {c->mom_decay[0], c->mom_decay[1], c->mom_decay[2], c->rms_decay,
+                      c->fac_decay[0], c->fac_decay[1], c->fac_decay[2]};
+  for (float v : d)
+    if (!(v >= 0.f && v < 1.f)) return bad("every decay must be in [0, 1)");
+  if (!(c->eps_acc >= 0.f) || !(c->eps_norm >= 0.f)) return bad("eps_acc and eps_norm must be >= 0");
+  if (!std::isfinite(c->exp_mult) || !std::isfinite(c->step_mult)) return bad("exp_mult/step_mult must be finite");
+  if (c->kind == LOPT_VELO) {
+    if (c->lstm_hidden < 1 || c->lstm_hidden > 1024) return bad("config.lstm_hidden must be in [1, 1024]");
+    if (c->n_bank < 1 || c->n_bank > 1024) return bad("config.n_bank must be in [1, 1024]");
+  }
+  return true;
+}
+
+struct Plan {
+  std::vector<lopt_tensor_desc> descs;
+  std::vector<TensorDev> tensors;   // pointers filled per call
+  std::vector<TileDev> tiles;
+  std::vector<RcItemDev> rcitems;
+  std::vector<size_t> state_bytes;
+  uint64_t oLstmU = 0, oHNew = 0;   // VeLO scratch (floats)
+  uint64_t ws_floats = 0;
+};
+
+}  // namespace
+
+struct lopt_ctx {
+  lopt_config cfg;
+  int device = 0;
+  int HP = 0, F = 0, P = 0;
+  float* d_weights = nullptr;      // the uploaded blob
+  float* d_tail = nullptr;         // small_fc_lopt: padded W2 b2 W3 b3
+  WeightsDev W{};
+  // cached plan + device tables
+  Plan plan;
+  bool plan_valid = false;
+  void* d_tables = nullptr;
+  size_t d_tables_bytes = 0;
+  TensorDev* d_tensors = nullptr;
+  TileDev* d_tiles = nullptr;
+  RcItemDev* d_rcitems = nullptr;
+  bool static_uploaded = false;    // tiles + rcitems are on the device
+  std::vector<TensorDev> last_tensors;  // what d_tensors currently holds
+  bool tensors_uploaded = false;
+  void* h_stage = nullptr;         // pinned staging
+  size_t h_stage_bytes = 0;
+  hipEvent_t stage_ev = nullptr;
+  bool stage_pending = false;
+  std::string err;
+};
+
+namespace {
+
+lopt_status fail(lopt_ctx* ctx, lopt_status st, const std::string& msg) {
+  if (ctx) ctx->err = msg;
+  g_last_error = msg;
+  return st;
+}
+
+#define HIP_TRY(ctx, call)                                                                   \
+  do {                                                                                       \
+    hipError_t e_ = (call);                                                                  \
+    if (e_ != hipSuccess)                                                                    \
+      return fail(ctx, e_ == hipErrorOutOfMemory ? LOPT_ENOMEM : LOPT_EHIP,                  \
+                  std::string(#call) + ": " + hipGetErrorString(e_));                        \
+  } while (0)
+
+lopt_status check_descs(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* d) {
+  if (n > 0 && !d) return fail(ctx, LOPT_EINVAL, "descs_host is null");
+  if (n > (size_t)1 << 24) return fail(ctx, LOPT_EINVAL, "too many tensors");
+  for (size_t i = 0; i < n; ++i) {
+    if (d[i].rows < 1 || d[i].cols < 1 || d[i].rows > 0x7fffffffLL || d[i].cols > 0x7fffffffLL ||
+        d[i].rows * d[i].cols > 0x7fffffffLL) {
+      char buf[160];
+      snprintf(buf, sizeof buf, "tensor %zu: rows=%lld cols=%lld outside [1, 2^31-1] elements", i,
+               (long long)d[i].rows, (long long)d[i].cols);
+      return fail(ctx, LOPT_ESHAPE, buf);
+    }
+    if (d[i].ndim < 1) return fail(ctx, LOPT_EINVAL, "tensor ndim must be >= 1");
+  }
+  return LOPT_OK;
+}
+
+// Lay out tiles, row/column blocks and workspace regions for a tensor list.
+void build_plan(const lopt_ctx* ctx, size_t n, const lopt_tensor_desc* d, Plan* pl) {
+  pl->descs.assign(d, d + n);
+  pl->tensors.assign(n, TensorDev{});
+  pl->tiles.clear();
+  pl->rcitems.clear();
+  pl->state_bytes.assign(n, 0);
+  const bool velo = ctx->cfg.kind == LOPT_VELO;
+  const int HP = ctx->HP;
+  const uint64_t prep_floats = (uint64_t)(LOPT_D_VELO + 1) * HP + (uint64_t)HP * HP + HP + 2 * HP + 2;
+  uint64_t off = 0;
+  auto take = [&](uint64_t nfloats) { uint64_t o = off; off = align64(off + nfloats); return o; };
+  if (velo) {
+    pl->oLstmU = take((uint64_t)n * kLstmInPad);
+    pl->oHNew = take((uint64_t)n * ctx->cfg.lstm_hidden);
+  }
+  for (size_t i = 0; i < n; ++i) {
+    TensorDev& T = pl->tensors[i];
+    const int m = (int)d[i].rows, nn = (int)d[i].cols;
+    const uint64_t N = (uint64_t)m * nn;
+    T.m = m; T.n = nn;
+    T.padN = pad4(N); T.padm = pad4(m); T.padn = pad4(nn);
+    T.padH = velo ? pad4(ctx->cfg.lstm_hidden) : 0;
+    T.ndim = d[i].ndim;
+    T.vec = (nn % 4 == 0) ? 1 : 0;
+    const int units = (m + kRowUnit - 1) / kRowUnit;
+    const int q = (units + kMaxRowTiles - 1) / kMaxRowTiles;
+    T.TR = kRowUnit * (q < 1 ? 1 : q);
+    T.nrt = (m + T.TR - 1) / T.TR;
+    T.nct = (nn + kTileCols - 1) / kTileCols;
+    T.tile0 = (int)pl->tiles.size();
+    for (int ti = 0; ti < T.nrt; ++ti)
+      for (int tj = 0; tj < T.nct; ++tj) pl->tiles.push_back(TileDev{(int)i, ti, tj, 0});
+    T.nrblk = (m + kBlock - 1) / kBlock;
+    T.ncblk = (nn + kBlock - 1) / kBlock;
+    T.rc0 = (int)pl->rcitems.size();
+    for (int b = 0; b < T.nrblk; ++b) pl->rcitems.push_back(RcItemDev{(int)i, 0, b, 0});
+    for (int b = 0; b < T.ncblk; ++b) pl->rcitems.push_back(RcItemDev{(int)i, 1, b, 0});
+    T.oRowPart = take((uint64_t)T.nct * m);
+    T.oColPart = take((uint64_t)T.nrt * nn);
+    T.oRR = take(3ull * T.padm);
+    T.oRC = take(3ull * T.padn);
+    T.oRcPart = take((uint64_t)(T.nrblk + T.ncblk) * kRcStride);
+    T.oStatPart = take((uint64_t)T.nrt * T.nct * kStatStride);
+    T.oStats = take(kStatsPerTensor);
+    T.oScale = take(kStatsPerTensor);
+    T.oPrep = take(prep_floats);
+    pl->state_bytes[i] = sizeof(float) * (4ull * T.padN + 3ull * T.padm + 3ull * T.padn + 2ull * T.padH);
+  }
+  pl->ws_floats = off;
+}
+
+bool same_descs(const Plan& pl, size_t n, const lopt_tensor_desc* d) {
+  if (pl.descs.size() != n) return false;
+  for (size_t i = 0; i < n; ++i)
+    if (pl.descs[i].ndim != d[i].ndim || pl.descs[i].rows != d[i].rows || pl.descs[i].cols != d[i].cols)
+      return false;
+  return true;
+}
+
+lopt_status ensure_plan(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* d) {
+  if (ctx->plan_valid && same_descs(ctx->plan, n, d)) return LOPT_OK;
+  try {
+    build_plan(ctx, n, d, &ctx->plan);
+  } catch (const std::bad_alloc&) {
+    ctx->plan_valid = false;
+    return fail(ctx, LOPT_ENOMEM, "out of host memory while planning");
+  }
+  ctx->plan_valid = true;
+  ctx->static_uploaded = false;
+  ctx->tensors_uploaded = false;
+  return LOPT_OK;
+}
+
+// Make sure the device tables exist and hold the current plan and pointers.
+lopt_status upload_tables(lopt_ctx* ctx, hipStream_t stream) {
+  Plan& pl = ctx->plan;
+  const size_t nT = pl.tensors.size(), nTi = pl.tiles.size(), nRc = pl.rcitems.size();
+  const size_t bT = align64(nT * sizeof(TensorDev)), bTi = align64(nTi * sizeof(TileDev)),
+               bRc = align64(nRc * sizeof(RcItemDev));
+  const size_t need = bT + bTi + bRc;
+  if (need == 0) return LOPT_OK;
+  if (need > ctx->d_tables_bytes) {
+    if (ctx->stage_pending) { HIP_TRY(ctx, hipEventSynchronize(ctx->stage_ev)); ctx->stage_pending = false; }
+    if (ctx->d_tables) { HIP_TRY(ctx, hipStreamSynchronize(stream)); HIP_TRY(ctx, hipFree(ctx->d_tables)); ctx->d_tables = nullptr; }
+    ctx->d_tables_bytes = 0;
+    HIP_TRY(ctx, hipMalloc(&ctx->d_tables, need));
+    ctx->d_tables_bytes = need;
+    ctx->static_uploaded = false;
+    ctx->tensors_uploaded = false;
+  }
+  if (need > ctx->h_stage_bytes) {
+    if (ctx->stage_pending) { HIP_TRY(ctx, hipEventSynchronize(ctx->stage_ev)); ctx->stage_pending = false; }
+    if (ctx->h_stage) { HIP_TRY(ctx, hipHostFree(ctx->h_stage)); ctx->h_stage = nullptr; }
+    ctx->h_stage_bytes = 0;
+    HIP_TRY(ctx, hipHostMalloc(&ctx->h_stage, need, hipHostMallocDefault));
+    ctx->h_stage_bytes = need;
+  }
+  char* dbase = (char*)ctx->d_tables;
+  ctx->d_tensors = (TensorDev*)dbase;
+  ctx->d_tiles = (TileDev*)(dbase + bT);
+  ctx->d_rcitems = (RcItemDev*)(dbase + bT + bTi);
+  const bool need_tensors = !ctx->tensors_uploaded || ctx->last_tensors.size() != nT ||
+                            memcmp(ctx->last_tensors.data(), pl.tensors.data(), nT * sizeof(TensorDev)) != 0;
+  const bool need_static = !ctx->static_uploaded;
+  if (!need_tensors && !need_static) return LOPT_OK;
+  if (ctx->stage_pending) { HIP_TRY(ctx, hipEventSynchronize(ctx->stage_ev)); ctx->stage_pending = false; }
+  char* hbase = (char*)ctx->h_stage;
+  if (need_tensors) {
+    memcpy(hbase, pl.tensors.data(), nT * sizeof(TensorDev));
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->d_tensors, hbase, nT * sizeof(TensorDev), hipMemcpyHostToDevice, stream));
+    ctx->last_tensors = pl.tensors;
+    ctx->tensors_uploaded = true;
+  }
+  if (need_static) {
+    memcpy(hbase + bT, pl.tiles.data(), nTi * sizeof(TileDev));
+    memcpy(hbase + bT + bTi, pl.rcitems.data(), nRc * sizeof(RcItemDev));
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->d_tiles, hbase + bT, nTi * sizeof(TileDev) , hipMemcpyHostToDevice, stream));
+    if (nRc) HIP_TRY(ctx, hipMemcpyAsync(ctx->d_rcitems, hbase + bT + bTi, nRc * sizeof(RcItemDev), hipMemcpyHostToDevice, stream));
+    ctx->static_uploaded = true;
+  }
+  HIP_TRY(ctx, hipEventRecord(ctx->stage_ev, stream));
+  ctx->stage_pending = true;
+  return LOPT_OK;
+}
+
+StepArgs make_args(const lopt_ctx* ctx, int64_t step, float lr, float wd, int n_tensors) {
+  StepArgs A{};
+  const lopt_config& c = ctx->cfg;
+  for (int i = 0; i < 3; ++i) { A.mom_decay[i] = c.mom_decay[i]; A.fac_decay[i] = c.fac_decay[i]; }
+  A.rms_decay = c.rms_decay;
+  A.eps_acc = c.eps_acc; A.eps_norm = c.eps_norm;
+  A.exp_mult = c.exp_mult; A.step_mult = c.step_mult;
+  A.lr = lr; A.wd = wd;
+  A.step = (long long)step;
+  A.kind = (int)c.kind; A.H = (int)c.hidden; A.HP = ctx->HP; A.F = ctx->F;
+  A.HL = (int)c.lstm_hidden; A.K = (int)c.n_bank; A.P = ctx->P;
+  A.n_tensors = n_tensors;
+  return A;
+}
+
+}  // namespace
+
+extern "C" {
+
+lopt_status lopt_default_config(uint32_t kind, lopt_config* cfg) {
+  if (!cfg) return fail(nullptr, LOPT_EINVAL, "cfg is null");
+  if (kind != LOPT_SMALL_FC && kind != LOPT_VELO) return fail(nullptr, LOPT_EINVAL, "unknown kind");
+  memset(cfg, 0, sizeof *cfg);
+  cfg->struct_size = sizeof(lopt_config);
+  cfg->kind = kind;
+  cfg->hidden = kind == LOPT_SMALL_FC ? 32 : 4;
+  cfg->mom_decay[0] = 0.9f; cfg->mom_decay[1] = 0.99f; cfg->mom_decay[2] = 0.999f;
+  cfg->rms_decay = 0.999f;
+  cfg->fac_decay[0] = 0.9f; cfg->fac_decay[1] = 0.99f; cfg->fac_decay[2] = 0.999f;
+  cfg->eps_acc = 1e-16f;
+  cfg->eps_norm = 1e-30f;
+  cfg->exp_mult = 0.01f;
+  cfg->step_mult = 0.01f;
+  cfg->lstm_hidden = 512;
+  cfg->n_bank = 256;
+  return LOPT_OK;
+}
+
+size_t lopt_weights_count(const lopt_config* c) {
+  if (!config_ok(c, nullptr)) return 0;
+  if (c->kind == LOPT_SMALL_FC) return mlp_count(LOPT_D_SMALL_FC, (int)c->hidden);
+  const size_t HL = c->lstm_hidden, K = c->n_bank, P = mlp_count(LOPT_D_VELO, (int)c->hidden);
+  return (size_t)LOPT_VELO_LSTM_IN * 4 * HL + HL * 4 * HL + 4 * HL + HL * K + K + K * P;
+}
+
+lopt_status lopt_create(const lopt_config* cfg, const float* weights_host, size_t n_weights, lopt_ctx** out) {
+  std::string why;
+  if (!out) return fail(nullptr, LOPT_EINVAL, "out is null");
+  if (!config_ok(cfg, &why)) return fail(nullptr, LOPT_EINVAL, why);
+  if (!weights_host) return fail(nullptr, LOPT_EINVAL, "weights_host is null");
+  const size_t want = lopt_weights_count(cfg);
+  if (n_weights != want) {
+    char buf[128];
+    snprintf(buf, sizeof buf, "n_weights=%zu but this configuration needs %zu floats", n_weights, want);
+    return fail(nullptr, LOPT_ESTATE, buf);
+  }
+  lopt_ctx* ctx = new (std::nothrow) lopt_ctx();
+  if (!ctx) return fail(nullptr, LOPT_ENOMEM, "out of host memory");
+  ctx->cfg = *cfg;
+  const int H = (int)cfg->hidden;
+  ctx->HP = padded_hidden(H);
+  ctx->F = cfg->kind == LOPT_SMALL_FC ? LOPT_N_ELEM_FEATS : LOPT_D_VELO;
+  ctx->P = (int)mlp_count(LOPT_D_VELO, H);
+  lopt_status st = LOPT_OK;
+  auto cleanup = [&](lopt_status s) { std::string m = ctx->err; lopt_destroy(ctx); g_last_error = m; return s; };
+#define CREATE_TRY(call)                                                                      \
+  do {                                                                                        \
+    hipError_t e_ = (call);                                                                   \
+    if (e_ != hipSuccess) {                                                                   \
+      fail(ctx, e_ == hipErrorOutOfMemory ? LOPT_ENOMEM : LOPT_EHIP,                          \
+           std::string(#call) + ": " + hipGetErrorString(e_));                                \
+      return cleanup(e_ == hipErrorOutOfMemory ? LOPT_ENOMEM : LOPT_EHIP);                    \
+    }                                                                                         \
+  } while (0)
+  CREATE_TRY(hipGetDevice(&ctx->device));
+  CREATE_TRY(hipMalloc((void**)&ctx->d_weights, n_weights * sizeof(float)));
+  CREATE_TRY(hipMemcpy(ctx->d_weights, weights_host, n_weights * sizeof(float), hipMemcpyHostToDevice));
+  CREATE_TRY(hipEventCreateWithFlags(&ctx->stage_ev, hipEventDisableTiming));
+  if (cfg->kind == LOPT_SMALL_FC) {
+    const int HP = ctx->HP;
+    std::vector<float> tail((size_t)HP * HP + HP + 2 * HP + 2, 0.f);
+    const float* W2 = weights_host + (size_t)LOPT_D_SMALL_FC * H + H;
+    const float* b2 = W2 + (size_t)H * H;
+    const float* W3 = b2 + H;
+    const float* b3 = W3 + 2 * H;
+    for (int a = 0; a < H; ++a)
+      for (int u = 0; u < H; ++u) tail[(size_t)a * HP + u] = W2[a * H + u];
+    for (int u = 0; u < H; ++u) tail[(size_t)HP * HP + u] = b2[u];
+    for (int a = 0; a < H; ++a) { tail[(size_t)HP * HP + HP + 2 * a] = W3[2 * a]; tail[(size_t)HP * HP + HP + 2 * a + 1] = W3[2 * a + 1]; }
+    tail[(size_t)HP * HP + HP + 2 * HP] = b3[0];
+    tail[(size_t)HP * HP + HP + 2 * HP + 1] = b3[1];
+    CREATE_TRY(hipMalloc((void**)&ctx->d_tail, tail.size() * sizeof(float)));
+    CREATE_TRY(hipMemcpy(ctx->d_tail, tail.data(), tail.size() * sizeof(float), hipMemcpyHostToDevice));
+    ctx->W.mlp = ctx->d_weights;
+    ctx->W.mlp_tail = ctx->d_tail;
+  } else {
+    const size_t HL = cfg->lstm_hidden, K = cfg->n_bank;
+    const float* w = ctx->d_weights;
+    ctx->W.Wx = w; w += (size_t)LOPT_VELO_LSTM_IN * 4 * HL;
+    ctx->W.Wh = w; w += HL * 4 * HL;
+    ctx->W.b = w; w += 4 * HL;
+    ctx->W.Wa = w; w += HL * K;
+    ctx->W.ba = w; w += K;
+    ctx->W.B = w;
+  }
+#undef CREATE_TRY
+  (void)st;
+  *out = ctx;
+  return LOPT_OK;
+}
+
+void lopt_destroy(lopt_ctx* ctx) {
+  if (!ctx) return;
+  if (ctx->d_weights) (void)hipFree(ctx->d_weights);
+  if (ctx->d_tail) (void)hipFree(ctx->d_tail);
+  if (ctx->d_tables) (void)hipFree(ctx->d_tables);
+  if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
+  if (ctx->stage_ev) (void)hipEventDestroy(ctx->stage_ev);
+  delete ctx;
+}
+
+lopt_status lopt_state_bytes(const lopt_ctx* cctx, size_t n, const lopt_tensor_desc* descs, size_t* per_tensor,
+                             size_t* workspace_bytes) {
+  lopt_ctx* ctx = const_cast<lopt_ctx*>(cctx);
+  if (!ctx) return fail(nullptr, LOPT_EINVAL, "ctx is null");
+  lopt_status st = check_descs(ctx, n, descs);
+  if (st != LOPT_OK) return st;
+  Plan tmp;
+  const Plan* pl = &tmp;
+  if (ctx->plan_valid && same_descs(ctx->plan, n, descs)) pl = &ctx->plan;
+  else {
+    try { build_plan(ctx, n, descs, &tmp); } catch (const std::bad_alloc&) { return fail(ctx, LOPT_ENOMEM, "out of host memory while planning"); }
+  }
+  if (per_tensor) for (size_t i = 0; i < n; ++i) per_tensor[i] = pl->state_bytes[i];
+  if (workspace_bytes) *workspace_bytes = (size_t)(pl->ws_floats * sizeof(float)) + 256;
+  return LOPT_OK;
+}
+
+lopt_status lopt_stats_offsets(const lopt_ctx* cctx, size_t n, const lopt_tensor_desc* descs, size_t* offsets) {
+  lopt_ctx* ctx = const_cast<lopt_ctx*>(cctx);
+  if (!ctx) return fail(nullptr, LOPT_EINVAL, "ctx is null");
+  if (n > 0 && !offsets) return fail(ctx, LOPT_EINVAL, "offsets_bytes is null");
+  lopt_status st = check_descs(ctx, n, descs);
+  if (st != LOPT_OK) return st;
+  Plan tmp;
+  const Plan* pl = &tmp;
+  if (ctx->plan_valid && same_descs(ctx->plan, n, descs)) pl = &ctx->plan;
+  else {
+    try { build_plan(ctx, n, descs, &tmp); } catch (const std::bad_alloc&) { return fail(ctx, LOPT_ENOMEM, "out of host memory while planning"); }
+  }
+  for (size_t i = 0; i < n; ++i) offsets[i] = (size_t)pl->tensors[i].oStats * sizeof(float);
+  return LOPT_OK;
+}
+
+static lopt_status check_ptrs(lopt_ctx* ctx, size_t n, const void* const* arr, const char* name) {
+  if (n > 0 && !arr) return fail(ctx, LOPT_EINVAL, std::string(name) + " is null");
+  for (size_t i = 0; i < n; ++i) {
+    if (!arr[i]) return fail(ctx, LOPT_EINVAL, std::string(name) + "[" + std::to_string(i) + "] is null");
+    if ((uintptr_t)arr[i] & 15) return fail(ctx, LOPT_EINVAL, std::string(name) + "[" + std::to_string(i) + "] is not 16-byte aligned");
+  }
+  return LOPT_OK;
+}
+
+lopt_status lopt_init_state(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, void* const* state, void* workspace,
+                            void* hip_stream) {
+  (void)workspace;
+  if (!ctx) return fail(nullptr, LOPT_EINVAL, "ctx is null");
+  lopt_status st = check_descs(ctx, n, descs);
+  if (st != LOPT_OK) return st;
+  st = check_ptrs(ctx, n, (const void* const*)state, "state_host");
+  if (st != LOPT_OK) return st;
+  if (n == 0) return LOPT_OK;
+  st = ensure_plan(ctx, n, descs);
+  if (st != LOPT_OK) return st;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  for (size_t i = 0; i < n; ++i) {
+    TensorDev& T = ctx->plan.tensors[i];
+    T.st = (float*)state[i];
+  }
+  st = upload_tables(ctx, stream);
+  if (st != LOPT_OK) return st;
+  Launch L{ctx->d_tensors, ctx->d_tiles, ctx->d_rcitems, nullptr, (int)n, (int)ctx->plan.tiles.size(),
+           (int)ctx->plan.rcitems.size()};
+  StepArgs A = make_args(ctx, 0, 0.f, 0.f, (int)n);
+  launch_fill_zero(L, A, stream);
+  HIP_TRY(ctx, hipGetLastError());
+  return LOPT_OK;
+}
+
+lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, float* const* params,
+                      const float* const* grads, void* const* state, void* workspace, int64_t step, float lr,
+                      float weight_decay, void* hip_stream) {
+  if (!ctx) return fail(nullptr, LOPT_EINVAL, "ctx is null");
+  lopt_status st = check_descs(ctx, n, descs);
+  if (st != LOPT_OK) return st;
+  if (step < 0) return fail(ctx, LOPT_EINVAL, "step must be >= 0");
+  if (!std::isfinite(lr) || !std::isfinite(weight_decay)) return fail(ctx, LOPT_EINVAL, "lr and weight_decay must be finite");
+  if ((st = check_ptrs(ctx, n, (const void* const*)params, "params_host")) != LOPT_OK) return st;
+  if ((st = check_ptrs(ctx, n, (const void* const*)grads, "grads_host")) != LOPT_OK) return st;
+  if ((st = check_ptrs(ctx, n, (const void* const*)state, "state_host")) != LOPT_OK) return st;
+  if (n == 0) return LOPT_OK;
+  if (!workspace) return fail(ctx, LOPT_EINVAL, "workspace is null");
+  if ((uintptr_t)workspace & 15) return fail(ctx, LOPT_EINVAL, "workspace is not 16-byte aligned");
+  if ((st = ensure_plan(ctx, n, descs)) != LOPT_OK) return st;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  Plan& pl = ctx->plan;
+  for (size_t i = 0; i < n; ++i) {
+    TensorDev& T = pl.tensors[i];
+    T.p = params[i];
+    T.g = grads[i];
+    T.st = (float*)state[i];
+  }
+  if ((st = upload_tables(ctx, stream)) != LOPT_OK) return st;
+  // workspace base rounded up to 256 bytes (lopt_state_bytes adds the slack)
+  float* ws = (float*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255);
+  Launch L{ctx->d_tensors, ctx->d_tiles, ctx->d_rcitems, ws, (int)n, (int)pl.tiles.size(), (int)pl.rcitems.size()};
+  StepArgs A = make_args(ctx, step, lr, weight_decay, (int)n);
+  launch_rowcol_sums(L, A, stream);
+  launch_rc_update(L, A, stream);
+  launch_accum_stats(L, A, stream);
+  launch_finalize(L, A, ctx->W, ws + pl.oLstmU, stream);
+  if (ctx->cfg.kind == LOPT_VELO) {
+    launch_velo_lstm(L, A, ctx->W, ws + pl.oLstmU, ws + pl.oHNew, stream);
+    launch_velo_head(L, A, ctx->W, ws + pl.oHNew, stream);
+  }
+  if (apply_mfma_available(A)) launch_apply_mfma(L, A, ctx->W, stream);
+  else if (ctx->cfg.kind == LOPT_SMALL_FC) launch_apply_small_fc(L, A, ctx->W, stream);
+  else launch_apply_velo(L, A, ctx->W, stream);
+  HIP_TRY(ctx, hipGetLastError());
+  return LOPT_OK;
+}
+
+const char* lopt_last_error(const lopt_ctx* ctx) {
+  if (ctx) return ctx->err.c_str();
+  return g_last_error.c_str();
+}
+
+}  // extern "C"

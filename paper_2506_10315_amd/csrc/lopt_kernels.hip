@@ -1,0 +1,509 @@
+// gfx950 kernels of the learned-optimizer step (paper: section "Optimized Kernel Design").
+//
+// The paper's two CUDA kernels (feature statistics; fused apply) are re-cut here into a
+// fixed sequence of launches that each cover ALL tensors of the step through a table of
+// work items (one workgroup = one tile of one tensor):
+//   rowcol_sums  : per tile, sum of g^2 over the tile's columns (per row) and rows (per column)
+//   rc_update    : per row / per column: finish the means, update r_k, c_k, keep rsqrt(r_k+eps),
+//                  rsqrt(c_k+eps), and partial sums for the row/column-constant features
+//   accum_stats  : M_i, V update + per-tile sums of squares of the per-element features
+//   finalize     : per tensor, fixed-order reduction of all partials -> s_f, scale factors,
+//                  first MLP layer with the normalization folded in (small_fc_lopt), LSTM input (VeLO)
+//   velo_lstm, velo_head : the per-tensor hypernetwork (VeLO only)
+//   apply        : rebuild features, MLP, exponentiated update (lopt_apply_mfma.hip has the
+//                  matrix-core variant for hidden width 32)
+// A tile is TR rows x 256 columns; a wavefront owns whole rows of the tile (lane l holds the
+// four consecutive columns 4l..4l+3 as one float4), so row indices are wave-uniform and the
+// column factors are loaded once per tile.
+#include "lopt_internal.h"
+#include "lopt_device.h"
+
+namespace lopt {
+
+// ----------------------------------------------------------------------------- fill
+
+__global__ void __launch_bounds__(kBlock) k_fill_zero(const TensorDev* __restrict__ tensors, int H2) {
+  const TensorDev T = tensors[blockIdx.y];
+  size_t total = 4 * (size_t)T.padN + 3 * (size_t)T.padm + 3 * (size_t)T.padn + (size_t)H2 * T.padH;
+  size_t n4 = total / 4;  // every section is a multiple of 4 floats
+  float4* dst = reinterpret_cast<float4*>(T.st);
+  for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n4; i += (size_t)gridDim.x * kBlock)
+    dst[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+void launch_fill_zero(const Launch& L, const StepArgs& A, hipStream_t s) {
+  if (L.n_tensors == 0) return;
+  // grid.y is limited to 65535: loop over slabs of tensors
+  for (int t0 = 0; t0 < L.n_tensors; t0 += 32768) {
+    int nt = L.n_tensors - t0 < 32768 ? L.n_tensors - t0 : 32768;
+    hipLaunchKernelGGL(k_fill_zero, dim3(64, nt), dim3(kBlock), 0, s, L.tensors + t0,
+                       A.kind == LOPT_VELO ? 2 : 0);
+  }
+}
+
+// ----------------------------------------------------------------------------- rowcol_sums
+
+template <bool VEC>
+__device__ __forceinline__ void rowcol_tile(const TensorDev& T, const TileDev& tile, float* __restrict__ ws,
+                                            float (*colred)[kTileCols]) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = T.n, m = T.m;
+  const int col = tile.tj * kTileCols + 4 * lane;
+  const int r0 = tile.ti * T.TR;
+  const int r1 = min(r0 + T.TR, m);
+  float* __restrict__ rowpart = ws + T.oRowPart + (size_t)tile.tj * m;
+  float c0 = 0.f, c1 = 0.f, c2 = 0.f, c3 = 0.f;
+  int r = r0 + wave;
+  // two rows in flight per wavefront
+  for (; r + 4 < r1; r += 8) {
+    float4 a = load4<VEC>(T.g + (size_t)r * n, col, n);
+    float4 b = load4<VEC>(T.g + (size_t)(r + 4) * n, col, n);
+    float ax = a.x * a.x, ay = a.y * a.y, az = a.z * a.z, aw = a.w * a.w;
+    float bx = b.x * b.x, by = b.y * b.y, bz = b.z * b.z, bw = b.w * b.w;
+    c0 += ax; c1 += ay; c2 += az; c3 += aw;
+    c0 += bx; c1 += by; c2 += bz; c3 += bw;
+    float sa = wave_sum((ax + ay) + (az + aw));
+    float sb = wave_sum((bx + by) + (bz + bw));
+    if (lane == 0) { rowpart[r] = sa; rowpart[r + 4] = sb; }
+  }
+  for (; r < r1; r += 4) {
+    float4 a = load4<VEC>(T.g + (size_t)r * n, col, n);
+    float ax = a.x * a.x, ay = a.y * a.y, az = a.z * a.z, aw = a.w * a.w;
+    c0 += ax; c1 += ay; c2 += az; c3 += aw;
+    float sa = wave_sum((ax + ay) + (az + aw));
+    if (lane == 0) rowpart[r] = sa;
+  }
+  colred[wave][4 * lane + 0] = c0;
+  colred[wave][4 * lane + 1] = c1;
+  colred[wave][4 * lane + 2] = c2;
+  colred[wave][4 * lane + 3] = c3;
+  __syncthreads();
+  const int c = tile.tj * kTileCols + threadIdx.x;
+  if (c < n) {
+    float s = (colred[0][threadIdx.x] + colred[1][threadIdx.x]) + (colred[2][threadIdx.x] + colred[3][threadIdx.x]);
+    ws[T.oColPart + (size_t)tile.ti * n + c] = s;
+  }
+}
+
+__global__ void __launch_bounds__(kBlock) k_rowcol_sums(const TensorDev* __restrict__ tensors,
+                                                        const TileDev* __restrict__ tiles, float* __restrict__ ws) {
+  __shared__ float colred[4][kTileCols];
+  const TileDev tile = tiles[blockIdx.x];
+  const TensorDev& T = tensors[tile.tensor];
+  if (T.vec) rowcol_tile<true>(T, tile, ws, colred);
+  else rowcol_tile<false>(T, tile, ws, colred);
+}
+
+void launch_rowcol_sums(const Launch& L, const StepArgs&, hipStream_t s) {
+  if (L.n_tiles == 0) return;
+  hipLaunchKernelGGL(k_rowcol_sums, dim3(L.n_tiles), dim3(kBlock), 0, s, L.tensors, L.tiles, L.ws);
+}
+
+// ----------------------------------------------------------------------------- rc_update
+
+// Block-wide sums of NV values per thread; thread 0 of the block gets them in out[].
+template <int NV>
+__device__ __forceinline__ void block_sum(float (&v)[NV], float (*red)[4], float* out) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int q = 0; q < NV; ++q) {
+    float s = wave_sum(v[q]);
+    if (lane == 0) red[q][wave] = s;
+  }
+  __syncthreads();
+  if (threadIdx.x < NV) {
+    const int q = threadIdx.x;
+    out[q] = (red[q][0] + red[q][1]) + (red[q][2] + red[q][3]);
+  }
+}
+
+__global__ void __launch_bounds__(kBlock) k_rc_update(const TensorDev* __restrict__ tensors,
+                                                      const RcItemDev* __restrict__ items, float* __restrict__ ws,
+                                                      StepArgs A) {
+  __shared__ float red[9][4];
+  const RcItemDev it = items[blockIdx.x];
+  const TensorDev& T = tensors[it.tensor];
+  const int idx = it.blk * kBlock + threadIdx.x;
+  float v[9];
+#pragma unroll
+  for (int q = 0; q < 9; ++q) v[q] = 0.f;
+  float* st = T.st;
+  if (!it.is_col) {
+    if (idx < T.m) {
+      const float* part = ws + T.oRowPart + idx;
+      double acc = 0.0;
+      for (int j = 0; j < T.nct; ++j) acc += (double)part[(size_t)j * T.m];
+      const float R = (float)(acc / (double)T.n);
+#pragma unroll
+      for (int k = 0; k < 3; ++k) {
+        float* rk = st + 4 * (size_t)T.padN + (size_t)k * T.padm;
+        const float b = A.fac_decay[k];
+        const float r = b * rk[idx] + (1.0f - b) * R;
+        rk[idx] = r;
+        const float rr = rsqrtf(r + A.eps_acc);
+        ws[T.oRR + (size_t)k * T.padm + idx] = rr;
+        v[k] = r;
+        v[3 + k] = r * r;
+        v[6 + k] = rr * rr;
+      }
+    }
+  } else {
+    if (idx < T.n) {
+      const float* part = ws + T.oColPart + idx;
+      double acc = 0.0;
+      for (int i = 0; i < T.nrt; ++i) acc += (double)part[(size_t)i * T.n];
+      const float C = (float)(acc / (double)T.m);
+#pragma unroll
+      for (int k = 0; k < 3; ++k) {
+        float* ck = st + 4 * (size_t)T.padN + 3 * (size_t)T.padm + (size_t)k * T.padn;
+        const float b = A.fac_decay[k];
+        const float c = b * ck[idx] + (1.0f - b) * C;
+        ck[idx] = c;
+        const float rc = rsqrtf(c + A.eps_acc);
+        ws[T.oRC + (size_t)k * T.padn + idx] = rc;
+        v[3 + k] = c * c;
+        v[6 + k] = rc * rc;
+      }
+    }
+  }
+  const int slot = it.is_col ? T.nrblk + it.blk : it.blk;
+  block_sum<9>(v, red, ws + T.oRcPart + (size_t)slot * kRcStride);
+}
+
+void launch_rc_update(const Launch& L, const StepArgs& A, hipStream_t s) {
+  if (L.n_rcitems == 0) return;
+  hipLaunchKernelGGL(k_rc_update, dim3(L.n_rcitems), dim3(kBlock), 0, s, L.tensors, L.rcitems, L.ws, A);
+}
+
+// ----------------------------------------------------------------------------- accum_stats
+
+// The per-element features that need a statistic of their own (the row/column-constant ones
+// follow from r_k, c_k alone). rrc[k] = rsqrt(r_k[i]+eps) * rsqrt(c_k[j]+eps); the common
+// factor sqrt(mean(r_k)+eps) of the factored features is applied per tensor in k_finalize.
+template <bool VEC>
+__device__ __forceinline__ void accum_tile(const TensorDev& T, const TileDev& tile, float* __restrict__ ws,
+                                           const StepArgs& A, float (&acc)[kNStat]) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = T.n, m = T.m;
+  const int col = tile.tj * kTileCols + 4 * lane;
+  const int r0 = tile.ti * T.TR;
+  const int r1 = min(r0 + T.TR, m);
+  float4 rc[3];
+#pragma unroll
+  for (int k = 0; k < 3; ++k) rc[k] = load4<VEC>(ws + T.oRC + (size_t)k * T.padn, col, n);
+  float* __restrict__ M1 = T.st;
+  float* __restrict__ M2 = T.st + (size_t)T.padN;
+  float* __restrict__ M3 = T.st + 2 * (size_t)T.padN;
+  float* __restrict__ Vp = T.st + 3 * (size_t)T.padN;
+  const float b1 = A.mom_decay[0], b2 = A.mom_decay[1], b3 = A.mom_decay[2], b4 = A.rms_decay;
+  const float eps = A.eps_acc;
+  for (int r = r0 + wave; r < r1; r += 4) {
+    const size_t ro = (size_t)r * n;
+    const float4 g4 = load4<VEC>(T.g + ro, col, n);
+    const float4 p4 = load4<VEC>(T.p + ro, col, n);
+    const float4 m1 = load4<VEC>(M1 + ro, col, n);
+    const float4 m2 = load4<VEC>(M2 + ro, col, n);
+    const float4 m3 = load4<VEC>(M3 + ro, col, n);
+    const float4 v4 = load4<VEC>(Vp + ro, col, n);
+    float rr[3];
+#pragma unroll
+    for (int k = 0; k < 3; ++k) rr[k] = ws[T.oRR + (size_t)k * T.padm + r];
+    float o1[4], o2[4], o3[4], ov[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float g = get(g4, e), p = get(p4, e);
+      const float nm1 = b1 * get(m1, e) + (1.0f - b1) * g;
+      const float nm2 = b2 * get(m2, e) + (1.0f - b2) * g;
+      const float nm3 = b3 * get(m3, e) + (1.0f - b3) * g;
+      const float nv = b4 * get(v4, e) + (1.0f - b4) * (g * g);
+      o1[e] = nm1; o2[e] = nm2; o3[e] = nm3; ov[e] = nv;
+      if (col + e < n) {
+        const float rs = rsqrtf(nv + eps);
+        const float f0 = rr[0] * get(rc[0], e), f1 = rr[1] * get(rc[1], e), f2 = rr[2] * get(rc[2], e);
+        const float gc = fminf(fmaxf(g, -0.1f), 0.1f);
+        float t;
+        acc[0] += g * g;
+        acc[1] += p * p;
+        acc[2] += nm1 * nm1;
+        acc[3] += nm2 * nm2;
+        acc[4] += nm3 * nm3;
+        acc[5] += nv * nv;
+        t = nm1 * rs; acc[6] += t * t;
+        t = nm2 * rs; acc[7] += t * t;
+        t = nm3 * rs; acc[8] += t * t;
+        acc[9] += rs * rs;
+        t = g * f0; acc[10] += t * t;
+        t = g * f1; acc[11] += t * t;
+        t = g * f2; acc[12] += t * t;
+        t = nm1 * f0; acc[13] += t * t;
+        t = nm2 * f1; acc[14] += t * t;
+        t = nm3 * f2; acc[15] += t * t;
+        acc[16] += gc * gc;
+      }
+    }
+    store4<VEC>(M1 + ro, col, n, make_float4(o1[0], o1[1], o1[2], o1[3]));
+    store4<VEC>(M2 + ro, col, n, make_float4(o2[0], o2[1], o2[2], o2[3]));
+    store4<VEC>(M3 + ro, col, n, make_float4(o3[0], o3[1], o3[2], o3[3]));
+    store4<VEC>(Vp + ro, col, n, make_float4(ov[0], ov[1], ov[2], ov[3]));
+  }
+}
+
+__global__ void __launch_bounds__(kBlock) k_accum_stats(const TensorDev* __restrict__ tensors,
+                                                        const TileDev* __restrict__ tiles, float* __restrict__ ws,
+                                                        StepArgs A) {
+  __shared__ float red[kNStat][4];
+  const TileDev tile = tiles[blockIdx.x];
+  const TensorDev& T = tensors[tile.tensor];
+  float acc[kNStat];
+#pragma unroll
+  for (int q = 0; q < kNStat; ++q) acc[q] = 0.f;
+  if (T.vec) accum_tile<true>(T, tile, ws, A, acc);
+  else accum_tile<false>(T, tile, ws, A, acc);
+  const int lt = tile.ti * T.nct + tile.tj;
+  block_sum<kNStat>(acc, red, ws + T.oStatPart + (size_t)lt * kStatStride);
+}
+
+void launch_accum_stats(const Launch& L, const StepArgs& A, hipStream_t s) {
+  if (L.n_tiles == 0) return;
+  hipLaunchKernelGGL(k_accum_stats, dim3(L.n_tiles), dim3(kBlock), 0, s, L.tensors, L.tiles, L.ws, A);
+}
+
+// ----------------------------------------------------------------------------- finalize
+
+// One workgroup per tensor. Reduces every partial in a fixed order (double accumulation),
+// then writes s_f, the per-feature scale factors and the prepared first layer.
+__global__ void __launch_bounds__(kBlock) k_finalize(const TensorDev* __restrict__ tensors, float* __restrict__ ws,
+                                                     StepArgs A, WeightsDev W, float* __restrict__ lstm_u) {
+  __shared__ double part[8][32];
+  __shared__ double tot[48];
+  __shared__ float s_stats[32], s_scale[32], s_tfeat[LOPT_N_TIME];
+  const TensorDev& T = tensors[blockIdx.x];
+  if (threadIdx.x >= 64 && threadIdx.x < 64 + LOPT_N_TIME) {
+    // time features tanh(t/x) (feature table of small_fc_lopt, row "Time Features")
+    const double xs[LOPT_N_TIME] = {1, 3, 10, 30, 100, 300, 1000, 3000, 1e4, 3e4, 1e5};
+    s_tfeat[threadIdx.x - 64] = (float)tanh((double)A.step / xs[threadIdx.x - 64]);
+  }
+  const int q = threadIdx.x & 31, seg = threadIdx.x >> 5;
+  const int ntiles = T.nrt * T.nct;
+  // per-element statistics: 17 sums over the tiles
+  double a = 0.0;
+  if (q < kNStat) {
+    const float* sp = ws + T.oStatPart + q;
+    for (int i = seg; i < ntiles; i += 8) a += (double)sp[(size_t)i * kStatStride];
+  }
+  part[seg][q] = a;
+  __syncthreads();
+  if (threadIdx.x < 32) {
+    double s = 0.0;
+    for (int k = 0; k < 8; ++k) s += part[k][q];
+    tot[q] = s;
+  }
+  __syncthreads();
+  // row partials (9 sums over the row blocks) then column partials (slots 3..8 used)
+  a = 0.0;
+  if (q < 9) {
+    const float* rp = ws + T.oRcPart + q;
+    for (int i = seg; i < T.nrblk; i += 8) a += (double)rp[(size_t)i * kRcStride];
+  } else if (q >= 16 && q < 25) {
+    const float* cp = ws + T.oRcPart + (size_t)T.nrblk * kRcStride + (q - 16);
+    for (int i = seg; i < T.ncblk; i += 8) a += (double)cp[(size_t)i * kRcStride];
+  }
+  part[seg][q] = a;
+  __syncthreads();
+  if (threadIdx.x < 32) {
+    double s = 0.0;
+    for (int k = 0; k < 8; ++k) s += part[k][q];
+    if (q < 9) tot[17 + q] = s;                    // 17..19 sum r, 20..22 sum r^2, 23..25 sum 1/(r+eps)
+    else if (q >= 19 && q < 25) tot[26 + (q - 19)] = s;  // 26..28 sum c^2, 29..31 sum 1/(c+eps)
+  }
+  __syncthreads();
+  if (threadIdx.x < 32) {
+    const int f = threadIdx.x;
+    const double N = (double)T.m * (double)T.n;
+    double s = 0.0;
+    double pre = 1.0;  // factor between the raw feature the kernels build and the feature itself
+    if (f < 10) s = tot[f] / N;
+    else if (f < 13 || (f >= 25 && f < 28)) {
+      const int k = f < 13 ? f - 10 : f - 25;
+      const double rbar = tot[17 + k] / (double)T.m + (double)A.eps_acc;
+      s = tot[f < 13 ? f : f - 12] / N * rbar;
+      pre = sqrt(rbar);
+    } else if (f < 16) s = tot[20 + (f - 13)] / (double)T.m;
+    else if (f < 19) s = tot[26 + (f - 16)] / (double)T.n;
+    else if (f < 22) s = tot[23 + (f - 19)] / (double)T.m;
+    else if (f < 25) s = tot[29 + (f - 22)] / (double)T.n;
+    else if (f == 28) s = tot[16] / N;
+    const float sf = (float)s;
+    const float scale = (float)(pre / sqrt((double)sf + (double)A.eps_norm));
+    s_stats[f] = sf;
+    s_scale[f] = f < A.F ? scale : 0.f;
+    ws[T.oStats + f] = f < A.F ? sf : 0.f;
+    ws[T.oScale + f] = f < A.F ? scale : 0.f;
+  }
+  __syncthreads();
+  if (A.kind == LOPT_SMALL_FC) {
+    // first layer with the normalization folded in, hidden width padded with zeros to HP;
+    // the un-normalized time features only shift the bias.
+    const int H = A.H, HP = A.HP;
+    float* prep = ws + T.oPrep;
+    for (int i = threadIdx.x; i < LOPT_N_ELEM_FEATS * HP; i += kBlock) {
+      const int f = i / HP, u = i - f * HP;
+      prep[i] = u < H ? W.mlp[f * H + u] * s_scale[f] : 0.f;
+    }
+    for (int u = threadIdx.x; u < HP; u += kBlock) {
+      float b = 0.f;
+      if (u < H) {
+        b = W.mlp[LOPT_D_SMALL_FC * H + u];
+        for (int i = 0; i < LOPT_N_TIME; ++i) b += s_tfeat[i] * W.mlp[(LOPT_N_ELEM_FEATS + i) * H + u];
+      }
+      prep[LOPT_N_ELEM_FEATS * HP + u] = b;
+    }
+  } else {
+    // LSTM input: 0.05*ln(s_f + 1e-30), time features, one-hot of min(ndim, 4)
+    float* u = lstm_u + (size_t)blockIdx.x * kLstmInPad;
+    const int t = threadIdx.x;
+    if (t < LOPT_D_VELO) u[t] = 0.05f * logf(s_stats[t] + 1e-30f);
+    else if (t < LOPT_D_VELO + LOPT_N_TIME) u[t] = s_tfeat[t - LOPT_D_VELO];
+    else if (t < LOPT_VELO_LSTM_IN) {
+      const int nd = T.ndim < 4u ? (int)T.ndim : 4;
+      u[t] = (t - (LOPT_D_VELO + LOPT_N_TIME)) == nd ? 1.f : 0.f;
+    } else if (t < kLstmInPad) u[t] = 0.f;
+  }
+}
+
+void launch_finalize(const Launch& L, const StepArgs& A, const WeightsDev& W, float* lstm_u, hipStream_t s) {
+  if (L.n_tensors == 0) return;
+  hipLaunchKernelGGL(k_finalize, dim3(L.n_tensors), dim3(kBlock), 0, s, L.tensors, L.ws, A, W, lstm_u);
+}
+
+// ----------------------------------------------------------------------------- VeLO hypernetwork
+
+// One LSTM-cell step for a group of tensors. Workgroup = (group of kLstmTensorsPerBlock tensors,
+// slab of 64 hidden units); thread = (unit, quarter of the tensors' inputs is not split: each thread
+// owns one unit for all tensors of the group and computes its four gates).
+__global__ void __launch_bounds__(kWave) k_velo_lstm(const TensorDev* __restrict__ tensors, StepArgs A, WeightsDev W,
+                                                     const float* __restrict__ lstm_u, float* __restrict__ h_new) {
+  extern __shared__ float sh[];  // [kLstmTensorsPerBlock][kLstmInPad + HL]
+  const int HL = A.HL;
+  const int stride = kLstmInPad + HL;
+  const int t0 = blockIdx.x * kLstmTensorsPerBlock;
+  const int nt = min(kLstmTensorsPerBlock, A.n_tensors - t0);
+  for (int i = threadIdx.x; i < kLstmTensorsPerBlock * stride; i += kWave) {
+    const int tt = i / stride, k = i - tt * stride;
+    float v = 0.f;
+    if (tt < nt) {
+      if (k < kLstmInPad) v = lstm_u[(size_t)(t0 + tt) * kLstmInPad + k];
+      else {
+        const TensorDev& T = tensors[t0 + tt];
+        v = T.st[4 * (size_t)T.padN + 3 * (size_t)T.padm + 3 * (size_t)T.padn + (k - kLstmInPad)];
+      }
+    }
+    sh[i] = v;
+  }
+  __syncthreads();
+  const int u = blockIdx.y * kWave + threadIdx.x;
+  if (u >= HL) return;
+  float z[4][kLstmTensorsPerBlock];
+#pragma unroll
+  for (int gI = 0; gI < 4; ++gI) {
+    const float bb = W.b[gI * HL + u];
+#pragma unroll
+    for (int tt = 0; tt < kLstmTensorsPerBlock; ++tt) z[gI][tt] = bb;
+  }
+  const int G = 4 * HL;
+  for (int k = 0; k < LOPT_VELO_LSTM_IN; ++k) {
+    float w[4];
+#pragma unroll
+    for (int gI = 0; gI < 4; ++gI) w[gI] = W.Wx[(size_t)k * G + gI * HL + u];
+#pragma unroll
+    for (int tt = 0; tt < kLstmTensorsPerBlock; ++tt) {
+      const float x = sh[tt * stride + k];
+#pragma unroll
+      for (int gI = 0; gI < 4; ++gI) z[gI][tt] += x * w[gI];
+    }
+  }
+  for (int k = 0; k < HL; ++k) {
+    float w[4];
+#pragma unroll
+    for (int gI = 0; gI < 4; ++gI) w[gI] = W.Wh[(size_t)k * G + gI * HL + u];
+#pragma unroll
+    for (int tt = 0; tt < kLstmTensorsPerBlock; ++tt) {
+      const float x = sh[tt * stride + kLstmInPad + k];
+#pragma unroll
+      for (int gI = 0; gI < 4; ++gI) z[gI][tt] += x * w[gI];
+    }
+  }
+#pragma unroll
+  for (int tt = 0; tt < kLstmTensorsPerBlock; ++tt) {
+    if (tt < nt) {
+      const TensorDev& T = tensors[t0 + tt];
+      float* cl = T.st + 4 * (size_t)T.padN + 3 * (size_t)T.padm + 3 * (size_t)T.padn + T.padH;
+      const float ig = 1.f / (1.f + expf(-z[0][tt]));
+      const float fg = 1.f / (1.f + expf(-z[1][tt]));
+      const float gg = tanhf(z[2][tt]);
+      const float og = 1.f / (1.f + expf(-z[3][tt]));
+      const float c = fg * cl[u] + ig * gg;
+      cl[u] = c;
+      h_new[(size_t)(t0 + tt) * HL + u] = og * tanhf(c);
+    }
+  }
+}
+
+void launch_velo_lstm(const Launch& L, const StepArgs& A, const WeightsDev& W, const float* lstm_u, float* h_new,
+                      hipStream_t s) {
+  if (L.n_tensors == 0) return;
+  dim3 grid((L.n_tensors + kLstmTensorsPerBlock - 1) / kLstmTensorsPerBlock, (A.HL + kWave - 1) / kWave);
+  size_t shmem = (size_t)kLstmTensorsPerBlock * (kLstmInPad + A.HL) * sizeof(float);
+  hipLaunchKernelGGL(k_velo_lstm, grid, dim3(kWave), shmem, s, L.tensors, A, W, lstm_u, h_new);
+}
+
+// Head of the hypernetwork for one tensor: alpha = h W_a + b_a, theta = alpha B, written as the
+// prepared (zero-padded, first layer scaled) per-tensor MLP. Also stores the new h into the state.
+__global__ void __launch_bounds__(kBlock) k_velo_head(const TensorDev* __restrict__ tensors, float* __restrict__ ws,
+                                                      StepArgs A, WeightsDev W, const float* __restrict__ h_new) {
+  extern __shared__ float sh[];  // h[HL] then alpha[K]
+  const TensorDev& T = tensors[blockIdx.x];
+  const int HL = A.HL, K = A.K, H = A.H, HP = A.HP, F = LOPT_D_VELO;
+  float* sh_h = sh;
+  float* sh_a = sh + HL;
+  float* hstate = T.st + 4 * (size_t)T.padN + 3 * (size_t)T.padm + 3 * (size_t)T.padn;
+  for (int i = threadIdx.x; i < HL; i += kBlock) {
+    const float v = h_new[(size_t)blockIdx.x * HL + i];
+    sh_h[i] = v;
+    hstate[i] = v;
+  }
+  __syncthreads();
+  for (int q = threadIdx.x; q < K; q += kBlock) {
+    float a = W.ba[q];
+    for (int k = 0; k < HL; ++k) a += sh_h[k] * W.Wa[(size_t)k * K + q];
+    sh_a[q] = a;
+  }
+  // zero the padded layout first (padding must be zero)
+  float* prep = ws + T.oPrep;
+  const int prep_n = (F + 1) * HP + HP * HP + HP + 2 * HP + 2;
+  for (int i = threadIdx.x; i < prep_n; i += kBlock) prep[i] = 0.f;
+  __syncthreads();
+  const float* scale = ws + T.oScale;
+  const int P = A.P;
+  for (int i = threadIdx.x; i < P; i += kBlock) {
+    float th = 0.f;
+    for (int q = 0; q < K; ++q) th += sh_a[q] * W.B[(size_t)q * P + i];
+    // scatter from the compact layout (W1[F,H] b1[H] W2[H,H] b2[H] W3[H,2] b3[2]) to the padded one
+    int o = i, dst;
+    if (o < F * H) { const int f = o / H, u = o - f * H; dst = f * HP + u; th *= scale[f]; }
+    else if ((o -= F * H) < H) dst = F * HP + o;
+    else if ((o -= H) < H * H) { const int a = o / H, u = o - a * H; dst = (F + 1) * HP + a * HP + u; }
+    else if ((o -= H * H) < H) dst = (F + 1) * HP + HP * HP + o;
+    else if ((o -= H) < 2 * H) dst = (F + 1) * HP + HP * HP + HP + o;
+    else { o -= 2 * H; dst = (F + 1) * HP + HP * HP + HP + 2 * HP + o; }
+    prep[dst] = th;
+  }
+}
+
+void launch_velo_head(const Launch& L, const StepArgs& A, const WeightsDev& W, const float* h_new, hipStream_t s) {
+  if (L.n_tensors == 0) return;
+  size_t shmem = (size_t)(A.HL + A.K) * sizeof(float);
+  hipLaunchKernelGGL(k_velo_head, dim3(L.n_tensors), dim3(kBlock), shmem, s, L.tensors, L.ws, A, W, h_new);
+}
+
+}  // namespace lopt

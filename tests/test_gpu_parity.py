@@ -1,0 +1,60 @@
+"""GPU parity: the HIP path (through the C boundary) against the float64 CPU oracle, element by element.
+
+Tolerances (tests/harness.py): parameters <= 1e-4, accumulators <= 1e-5 in the metric
+max_i |a_i - b_i| / (|b_i| + rms(b)) per tensor; both sides use the same float32 inputs and scalars.
+"""
+import numpy as np
+import pytest
+
+import workloads as W
+from tests import harness as Hn
+
+pytestmark = pytest.mark.gpu
+
+
+def _specs(shapes):
+    return [W.TensorSpec(f"t{i}", tuple(s)) for i, s in enumerate(shapes)]
+
+
+def test_config1_small_fc_free_running():
+    wl = W.get_workload(1)
+    cfg = Hn.make_cfg("small_fc_lopt")
+    w = W.small_fc_weights(0, 32)
+    worst = Hn.run_free(Hn.Case(1, wl.tensors, wl.grad_kind), cfg, w, wl.steps, verbose=True)
+    print("config1 worst:", worst)
+
+
+ODD_SHAPES = [(7, 13), (5,), (1,), (3, 1), (300, 257), (65, 1000), (2, 3, 5), (1, 1, 33), (130, 260), (1030,)]
+
+
+@pytest.mark.parametrize("hidden", [3, 5, 12, 32])
+def test_small_fc_odd_shapes_and_hidden_widths(hidden):
+    cfg = Hn.make_cfg("small_fc_lopt", hidden=hidden)
+    w = Hn.random_weights(cfg, seed=hidden)
+    Hn.run_free(Hn.Case(101, _specs(ODD_SHAPES)), cfg, w, 4, lr_fn=lambda t: 0.5, wd=0.01)
+
+
+@pytest.mark.parametrize("hidden,lstm_hidden,n_bank", [(4, 16, 8), (2, 33, 5), (4, 512, 256), (7, 64, 16)])
+def test_velo_odd_shapes(hidden, lstm_hidden, n_bank):
+    cfg = Hn.make_cfg("velo", hidden=hidden, lstm_hidden=lstm_hidden, n_bank=n_bank)
+    w = Hn.random_weights(cfg, seed=3)
+    Hn.run_free(Hn.Case(102, _specs(ODD_SHAPES), "gauss_logscale"), cfg, w, 4, lr_fn=lambda t: 0.5, wd=0.01)
+
+
+def test_velo_config1_shapes_free_running_with_clip_active():
+    # gradients of order 0.1 so that the clipped-gradient feature differs from the gradient
+    cfg = Hn.make_cfg("velo")
+    w = W.velo_weights(0)
+
+    class BigGrad(Hn.Case):
+        def grad(self, i, step):
+            return (super().grad(i, step) * np.float32(100.0)).astype(np.float32)
+
+    Hn.run_free(BigGrad(103, W.config1_shapes()), cfg, w, 6, lr_fn=lambda t: W.lr_at(W.get_workload(3), t), wd=0.01)
+
+
+def test_tall_and_wide_tensors():
+    # tall: more than 64 row tiles' worth of rows (tile height grows); wide 1-D: many column tiles
+    cfg = Hn.make_cfg("small_fc_lopt")
+    w = W.small_fc_weights(1, 32)
+    Hn.run_free(Hn.Case(104, _specs([(9000, 256), (5504,), (4100, 8)]), "student_t3"), cfg, w, 3)
