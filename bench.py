@@ -1,0 +1,159 @@
+"""Benchmark of the learned-optimizer step on one MI355X.
+
+One "step" = one lopt_step() over the whole synthetic parameter set (all passes of the hot path),
+with parameters, gradients and optimizer state already resident in HBM. Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2|3|4|5] [--optimizer small_fc_lopt|velo]
+                  [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0
+MFMA_F32_PEAK_TFLOPS = 157.3
+VALU_F32_PEAK_TFLOPS = 157.3
+
+# Algorithmic work per element of the dominant pass:
+#   apply pass, small_fc_lopt hidden 32: MLP contraction 28*32 + 32*32 + 32*2 MACs = 3968 FLOP
+#   apply pass bytes: read g, p, M1..3, V (24 B) + write p (4 B) = 28 B
+#   accum_stats pass bytes: read g, p, M1..3, V (24 B) + write M1..3, V (16 B) = 40 B
+APPLY_FLOP_SMALL_FC = 2 * (28 * 32 + 32 * 32 + 32 * 2)
+APPLY_BYTES = 28
+ACCUM_BYTES = 40
+
+
+def cpu_baseline(config_id: int, optimizer: str):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload."""
+    import workloads as W
+    from oracle import lopt_oracle as O
+    wl = W.get_workload(config_id, optimizer)
+    kind = O.KIND_SMALL_FC if optimizer == "small_fc_lopt" else O.KIND_VELO
+    cfg = O.OracleConfig(kind=kind, hidden=32 if kind == O.KIND_SMALL_FC else 4)
+    weights = W.small_fc_weights(0, 32) if kind == O.KIND_SMALL_FC else W.velo_weights(0)
+    # sample: the tensors of the first transformer block (every shape class of the repeated part)
+    prefixes = ("blocks.0.", "h.0.", "layers.0.")
+    idx = [i for i, t in enumerate(wl.tensors) if t.name.startswith(prefixes)]
+    inputs = []
+    for i in idx:
+        s = wl.tensors[i]
+        inputs.append((W.init_param(config_id, i, s), W.grad(config_id, i, 0, s, wl.grad_kind), s.as_2d()[0]))
+    n_el = sum(p.size for p, _, _ in inputs)
+    t0 = time.perf_counter()
+    for p, g, nd in inputs:
+        st = O.init_state(*p.shape, cfg)
+        O.tensor_step(p, g, st, weights, cfg, 0, 1.0, 0.0, ndim=nd)
+    dt = time.perf_counter() - t0
+    try:
+        import threadpoolctl
+        cores = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": n_el / dt / 1e9, "unit": "Gparams/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"one oracle step over the {len(idx)} tensors of the first block "
+                      f"({n_el} elements) of {wl.name}, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--optimizer", default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build targets one GPU; --gpus must be 1 (no collectives, no sharding here)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads as W
+    import paper_2506_10315_amd as P
+
+    wl = W.get_workload(args.config, args.optimizer)
+    optimizer = wl.optimizer
+    dev = "cuda:0"
+    kind = P.LOPT_SMALL_FC if optimizer == "small_fc_lopt" else P.LOPT_VELO
+    cfg = P.default_config(kind)
+    weights = W.small_fc_weights(0, 32) if kind == P.LOPT_SMALL_FC else W.velo_weights(0)
+    shapes = [t.shape for t in wl.tensors]
+    n = len(shapes)
+    n_el = wl.numel
+    # inputs: seeded host draws, uploaded once; two gradient sets alternate between steps
+    params = [torch.from_numpy(W.init_param(args.config, i, t)).to(dev) for i, t in enumerate(wl.tensors)]
+    n_sets = 2 if n_el < 500_000_000 else 1
+    grads = [[torch.from_numpy(W.grad(args.config, i, s, t, wl.grad_kind)).to(dev) for i, t in enumerate(wl.tensors)]
+             for s in range(n_sets)]
+    opt = P.LearnedOptimizer(cfg, weights, shapes, device=dev)
+    step = 0
+
+    def run(k):
+        nonlocal step
+        for _ in range(k):
+            opt.step(params, grads[step % n_sets], lr=W.lr_at(wl, step % wl.steps), weight_decay=wl.weight_decay,
+                     step=step)
+            step += 1
+
+    run(args.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.steps)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    # second pass of the same K steps with HIP events around every launch (on the same stream)
+    opt.profile_enable(True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    run(args.steps)
+    torch.cuda.synchronize()
+    dt_prof = time.perf_counter() - t1
+    pass_ms, k = opt.profile_read()
+    opt.profile_enable(False)
+    pass_ms = {name: v / max(k, 1) for name, v in pass_ms.items()}
+    finite = all(bool(torch.isfinite(p).all()) for p in params[:8])
+
+    dominant = max(pass_ms, key=pass_ms.get)
+    dur_s = pass_ms[dominant] * 1e-3
+    if dominant == "apply" and optimizer == "small_fc_lopt":
+        bound, unit, peak = "mfma", "TFLOP/s", MFMA_F32_PEAK_TFLOPS
+        achieved = APPLY_FLOP_SMALL_FC * n_el / dur_s / 1e12
+    else:
+        bound, unit, peak = "hbm", "GB/s", HBM_PEAK_GBS
+        per = APPLY_BYTES if dominant == "apply" else ACCUM_BYTES if dominant == "accum_stats" else 4
+        achieved = per * n_el / dur_s / 1e9
+    roofline = {"bound": bound, "kernel": dominant, "achieved": achieved, "peak": peak, "unit": unit,
+                "frac": achieved / peak, "traffic": None,
+                "avg_launch_ms": pass_ms[dominant], "pass_ms": pass_ms,
+                "ms_per_step_with_events": dt_prof / args.steps * 1e3}
+    out = {
+        "metric": "optimizer-step throughput", "value": n_el / (dt / args.steps) / 1e9, "unit": "Gparams/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"config {args.config}: {optimizer} on {wl.name} shapes "
+                               f"({n} tensors, {n_el} fp32 elements), all tensors in one lopt_step",
+                   "optimizer": optimizer, "hidden": int(cfg.hidden)},
+        "finite": finite,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.config, optimizer)
+    opt.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

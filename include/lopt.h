@@ -158,6 +158,19 @@ lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs_hos
 lopt_status lopt_stats_offsets(const lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs_host,
                                size_t* offsets_bytes);
 
+/* Per-pass timing for benchmarks. lopt_step is a fixed sequence of LOPT_N_PASSES kernel launches
+ * (a pass that a configuration does not use records zero time):
+ *   0 rowcol_sums  1 rc_update  2 accum_stats  3 finalize  4 velo_lstm  5 velo_head  6 apply
+ * With profiling enabled, lopt_step brackets every launch with HIP events on the caller's stream.
+ * lopt_profile_read waits for the recorded events, adds up the elapsed milliseconds per pass over
+ * all steps since the last read (ms_per_pass[LOPT_N_PASSES], may not be null), stores the number of
+ * steps in *n_steps (may be null) and clears the record. lopt_pass_name returns a static string,
+ * NULL for an index out of range. Profiling is off by default; it does not change any result. */
+#define LOPT_N_PASSES 7
+lopt_status lopt_profile_enable(lopt_ctx* ctx, int on);
+lopt_status lopt_profile_read(lopt_ctx* ctx, double* ms_per_pass, uint64_t* n_steps);
+const char* lopt_pass_name(int pass);
+
 /* Message for the last non-OK status returned through this context ("" if none). With a
  * null ctx: the message of the last failed lopt_create / lopt_default_config on this thread. */
 const char* lopt_last_error(const lopt_ctx* ctx);

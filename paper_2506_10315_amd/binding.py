@@ -10,10 +10,12 @@ _LIB_PATH = os.path.join(_HERE, "liblopt.so")
 
 LOPT_SMALL_FC = 0
 LOPT_VELO = 1
+N_PASSES = 7
 _STATUS = {0: "LOPT_OK", 1: "LOPT_EINVAL", 2: "LOPT_ESHAPE", 3: "LOPT_ESTATE", 4: "LOPT_ENOMEM", 5: "LOPT_EHIP"}
 
 EXPORTS = ["lopt_default_config", "lopt_weights_count", "lopt_create", "lopt_destroy", "lopt_state_bytes",
-           "lopt_init_state", "lopt_step", "lopt_stats_offsets", "lopt_last_error"]
+           "lopt_init_state", "lopt_step", "lopt_stats_offsets", "lopt_last_error",
+           "lopt_profile_enable", "lopt_profile_read", "lopt_pass_name"]
 
 
 class LoptError(RuntimeError):
@@ -66,6 +68,12 @@ def lib() -> C.CDLL:
     L.lopt_step.restype = C.c_int
     L.lopt_stats_offsets.argtypes = [vp, sz, C.POINTER(lopt_tensor_desc), C.POINTER(sz)]
     L.lopt_stats_offsets.restype = C.c_int
+    L.lopt_profile_enable.argtypes = [vp, C.c_int]
+    L.lopt_profile_enable.restype = C.c_int
+    L.lopt_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
+    L.lopt_profile_read.restype = C.c_int
+    L.lopt_pass_name.argtypes = [C.c_int]
+    L.lopt_pass_name.restype = C.c_char_p
     L.lopt_last_error.argtypes = [vp]
     L.lopt_last_error.restype = C.c_char_p
     _lib = L
@@ -142,6 +150,16 @@ class LearnedOptimizer:
                                    C.c_void_p(self.workspace.data_ptr()), t, lr, weight_decay,
                                    self._stream()), self._ctx)
         self.step_count = t + 1
+
+    def profile_enable(self, on: bool = True):
+        _check(lib().lopt_profile_enable(self._ctx, 1 if on else 0), self._ctx)
+
+    def profile_read(self):
+        """({pass name: total ms since the last read}, number of steps)."""
+        ms = (C.c_double * N_PASSES)()
+        k = C.c_uint64()
+        _check(lib().lopt_profile_read(self._ctx, ms, C.byref(k)), self._ctx)
+        return {lib().lopt_pass_name(i).decode(): float(ms[i]) for i in range(N_PASSES)}, int(k.value)
 
     def stats(self):
         """Per-tensor feature statistics left in the workspace by the last step (list of 1-D tensors)."""

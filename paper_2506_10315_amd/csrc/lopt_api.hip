@@ -79,6 +79,10 @@ struct lopt_ctx {
   size_t h_stage_bytes = 0;
   hipEvent_t stage_ev = nullptr;
   bool stage_pending = false;
+  // optional per-pass timing
+  bool profiling = false;
+  std::vector<hipEvent_t> prof_events;   // (LOPT_N_PASSES + 1) events per recorded step
+  size_t prof_steps = 0;
   std::string err;
 };
 
@@ -358,6 +362,7 @@ void lopt_destroy(lopt_ctx* ctx) {
   if (ctx->d_tables) (void)hipFree(ctx->d_tables);
   if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
   if (ctx->stage_ev) (void)hipEventDestroy(ctx->stage_ev);
+  for (hipEvent_t e : ctx->prof_events) (void)hipEventDestroy(e);
   delete ctx;
 }
 
@@ -457,19 +462,73 @@ lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, fl
   float* ws = (float*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255);
   Launch L{ctx->d_tensors, ctx->d_tiles, ctx->d_rcitems, ws, (int)n, (int)pl.tiles.size(), (int)pl.rcitems.size()};
   StepArgs A = make_args(ctx, step, lr, weight_decay, (int)n);
+  hipEvent_t* ev = nullptr;
+  if (ctx->profiling) {
+    const size_t need = (ctx->prof_steps + 1) * (LOPT_N_PASSES + 1);
+    while (ctx->prof_events.size() < need) {
+      hipEvent_t e;
+      HIP_TRY(ctx, hipEventCreate(&e));
+      ctx->prof_events.push_back(e);
+    }
+    ev = ctx->prof_events.data() + ctx->prof_steps * (LOPT_N_PASSES + 1);
+    ctx->prof_steps++;
+  }
+#define MARK(i) do { if (ev) HIP_TRY(ctx, hipEventRecord(ev[i], stream)); } while (0)
+  MARK(0);
   launch_rowcol_sums(L, A, stream);
+  MARK(1);
   launch_rc_update(L, A, stream);
+  MARK(2);
   launch_accum_stats(L, A, stream);
+  MARK(3);
   launch_finalize(L, A, ctx->W, ws + pl.oLstmU, stream);
+  MARK(4);
   if (ctx->cfg.kind == LOPT_VELO) {
     launch_velo_lstm(L, A, ctx->W, ws + pl.oLstmU, ws + pl.oHNew, stream);
+    MARK(5);
     launch_velo_head(L, A, ctx->W, ws + pl.oHNew, stream);
+    MARK(6);
+  } else {
+    MARK(5);
+    MARK(6);
   }
   if (apply_mfma_available(A)) launch_apply_mfma(L, A, ctx->W, stream);
   else if (ctx->cfg.kind == LOPT_SMALL_FC) launch_apply_small_fc(L, A, ctx->W, stream);
   else launch_apply_velo(L, A, ctx->W, stream);
+  MARK(7);
+#undef MARK
   HIP_TRY(ctx, hipGetLastError());
   return LOPT_OK;
+}
+
+lopt_status lopt_profile_enable(lopt_ctx* ctx, int on) {
+  if (!ctx) return fail(nullptr, LOPT_EINVAL, "ctx is null");
+  ctx->profiling = on != 0;
+  return LOPT_OK;
+}
+
+lopt_status lopt_profile_read(lopt_ctx* ctx, double* ms_per_pass, uint64_t* n_steps) {
+  if (!ctx) return fail(nullptr, LOPT_EINVAL, "ctx is null");
+  if (!ms_per_pass) return fail(ctx, LOPT_EINVAL, "ms_per_pass is null");
+  for (int i = 0; i < LOPT_N_PASSES; ++i) ms_per_pass[i] = 0.0;
+  for (size_t s = 0; s < ctx->prof_steps; ++s) {
+    hipEvent_t* ev = ctx->prof_events.data() + s * (LOPT_N_PASSES + 1);
+    HIP_TRY(ctx, hipEventSynchronize(ev[LOPT_N_PASSES]));
+    for (int i = 0; i < LOPT_N_PASSES; ++i) {
+      float ms = 0.f;
+      HIP_TRY(ctx, hipEventElapsedTime(&ms, ev[i], ev[i + 1]));
+      ms_per_pass[i] += (double)ms;
+    }
+  }
+  if (n_steps) *n_steps = ctx->prof_steps;
+  ctx->prof_steps = 0;
+  return LOPT_OK;
+}
+
+const char* lopt_pass_name(int pass) {
+  static const char* names[LOPT_N_PASSES] = {"rowcol_sums", "rc_update", "accum_stats", "finalize",
+                                             "velo_lstm", "velo_head", "apply"};
+  return pass >= 0 && pass < LOPT_N_PASSES ? names[pass] : nullptr;
 }
 
 const char* lopt_last_error(const lopt_ctx* ctx) {
