@@ -2,6 +2,7 @@
 // turns a tensor list into the device tables the kernels walk, and the launch sequence of a step.
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -79,6 +80,7 @@ struct lopt_ctx {
   size_t h_stage_bytes = 0;
   hipEvent_t stage_ev = nullptr;
   bool stage_pending = false;
+  bool force_valu = false;         // LOPT_FORCE_VALU=1 in the environment at create: skip the MFMA apply kernel
   // optional per-pass timing
   bool profiling = false;
   std::vector<hipEvent_t> prof_events;   // (LOPT_N_PASSES + 1) events per recorded step
@@ -303,6 +305,7 @@ lopt_status lopt_create(const lopt_config* cfg, const float* weights_host, size_
   lopt_ctx* ctx = new (std::nothrow) lopt_ctx();
   if (!ctx) return fail(nullptr, LOPT_ENOMEM, "out of host memory");
   ctx->cfg = *cfg;
+  { const char* e = getenv("LOPT_FORCE_VALU"); ctx->force_valu = e && e[0] == '1'; }
   const int H = (int)cfg->hidden;
   ctx->HP = padded_hidden(H);
   ctx->F = cfg->kind == LOPT_SMALL_FC ? LOPT_N_ELEM_FEATS : LOPT_D_VELO;
@@ -492,7 +495,7 @@ lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, fl
     MARK(5);
     MARK(6);
   }
-  if (apply_mfma_available(A)) launch_apply_mfma(L, A, ctx->W, stream);
+  if (!ctx->force_valu && apply_mfma_available(A)) launch_apply_mfma(L, A, ctx->W, stream);
   else if (ctx->cfg.kind == LOPT_SMALL_FC) launch_apply_small_fc(L, A, ctx->W, stream);
   else launch_apply_velo(L, A, ctx->W, stream);
   MARK(7);
