@@ -312,6 +312,19 @@ def tensor_step(p, g, st, weights, cfg: OracleConfig, t: int, lr: float, wd: flo
     return p_new
 
 
+def apply_rows(p, g, st, s, theta, cfg: OracleConfig, t: int, lr: float, wd: float, rows: slice) -> np.ndarray:
+    """New parameters of a slab of rows only, given the whole tensor's statistics `s` and the MLP
+    weights `theta` (accumulators in `st` already updated): the second half of tensor_step, for
+    spot checks on tensors too large to evaluate in full."""
+    p = np.asarray(p, F64)
+    n = p.shape[1]
+    Fc = construct_features(p, g, st, cfg, t, rows)
+    Fn = feature_normalization(Fc, s, cfg)
+    direction, magnitude = apply_lo(Fn, theta, cfg)
+    delta = delta_theta(direction, magnitude, cfg).reshape(-1, n)
+    return p[rows] - lr * (delta + wd * p[rows])
+
+
 def rel_err(a, b) -> float:
     """max_i |a_i - b_i| / (|b_i| + rms(b)): the error metric of the parity tests."""
     a = np.asarray(a, F64).ravel()

@@ -1,0 +1,128 @@
+"""GPU behaviour that is not numerical parity: determinism (doubles as the race detector), checkpoint /
+resume through the documented state layout, argument validation on the step path, empty lists."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+import workloads as W
+from tests import harness as Hn
+
+pytestmark = pytest.mark.gpu
+
+SHAPES = [(300, 257), (64, 256), (1030,), (5,), (520, 768)]
+
+
+def _run(kind, steps, device="cuda:0", resume_at=None, seed=0):
+    import torch
+    import paper_2506_10315_amd as P
+    cfg = Hn.make_cfg(kind) if kind == "small_fc_lopt" else Hn.make_cfg(kind, lstm_hidden=64, n_bank=32)
+    w = Hn.random_weights(cfg, seed)
+    specs = [W.TensorSpec(f"t{i}", s) for i, s in enumerate(SHAPES)]
+    case = Hn.Case(201, specs, "gauss_logscale")
+    opt = P.LearnedOptimizer(cfg, w, SHAPES, device=device)
+    p = [torch.from_numpy(case.p0(i)).to(device) for i in range(len(specs))]
+    for t in range(steps):
+        if resume_at is not None and t == resume_at:
+            # checkpoint = plain copies of params and state blobs; resume into a NEW context
+            torch.cuda.synchronize()
+            saved_p = [x.clone() for x in p]
+            saved_s = [x.clone() for x in opt.state]
+            opt.close()
+            opt = P.LearnedOptimizer(cfg, w, SHAPES, device=device)
+            for dst, src in zip(opt.state, saved_s):
+                dst.copy_(src)
+            p = saved_p
+        g = [torch.from_numpy(case.grad(i, t)).to(device) for i in range(len(specs))]
+        opt.step(p, g, lr=0.7, weight_decay=0.01, step=t)
+    torch.cuda.synchronize()
+    out = [x.cpu().numpy().copy() for x in p] + [x.cpu().numpy().copy() for x in opt.state]
+    opt.close()
+    return out
+
+
+@pytest.mark.parametrize("kind", ["small_fc_lopt", "velo"])
+def test_two_runs_are_bit_identical(kind):
+    a = _run(kind, 5)
+    b = _run(kind, 5)
+    for x, y in zip(a, b):
+        assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
+
+
+@pytest.mark.parametrize("kind", ["small_fc_lopt", "velo"])
+def test_checkpoint_resume_is_bit_identical(kind):
+    a = _run(kind, 6)
+    b = _run(kind, 6, resume_at=3)
+    for x, y in zip(a, b):
+        assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
+
+
+def test_step_argument_validation_leaves_everything_untouched():
+    import torch
+    import paper_2506_10315_amd as P
+    from paper_2506_10315_amd import binding as B
+    cfg = Hn.make_cfg("small_fc_lopt")
+    opt = P.LearnedOptimizer(cfg, W.small_fc_weights(0), [(8, 12)])
+    p = torch.full((8, 12), 0.5, device="cuda:0")
+    g = torch.full((8, 12), 1e-3, device="cuda:0")
+    L = P.lib()
+    ws = C.c_void_p(opt.workspace.data_ptr())
+    descs = opt._descs
+
+    def step(pp, gp, sp, workspace=ws, step=0, lr=1.0, wd=0.0, d=descs, n=1):
+        arr = lambda x: (C.c_void_p * 1)(x)
+        return L.lopt_step(opt._ctx, n, d, arr(pp), arr(gp), arr(sp), workspace, step, lr, wd, None)
+
+    sp = opt.state[0].data_ptr()
+    assert step(None, g.data_ptr(), sp) == 1
+    assert step(p.data_ptr(), None, sp) == 1
+    assert step(p.data_ptr(), g.data_ptr(), None) == 1
+    assert step(p.data_ptr() + 4, g.data_ptr(), sp) == 1 and b"aligned" in L.lopt_last_error(opt._ctx)
+    assert step(p.data_ptr(), g.data_ptr(), sp, workspace=None) == 1
+    assert step(p.data_ptr(), g.data_ptr(), sp, step=-1) == 1
+    assert step(p.data_ptr(), g.data_ptr(), sp, lr=float("nan")) == 1
+    assert step(p.data_ptr(), g.data_ptr(), sp, wd=float("inf")) == 1
+    bad = (B.lopt_tensor_desc * 1)()
+    bad[0].ndim, bad[0].rows, bad[0].cols = 2, 0, 12
+    assert step(p.data_ptr(), g.data_ptr(), sp, d=bad) == 2          # LOPT_ESHAPE
+    bad[0].rows, bad[0].cols = 1 << 20, 1 << 20
+    assert step(p.data_ptr(), g.data_ptr(), sp, d=bad) == 2
+    bad[0].ndim, bad[0].rows, bad[0].cols = 0, 8, 12
+    assert step(p.data_ptr(), g.data_ptr(), sp, d=bad) == 1
+    # an empty list is a valid no-op
+    assert L.lopt_step(opt._ctx, 0, None, None, None, None, None, 0, 1.0, 0.0, None) == 0
+    torch.cuda.synchronize()
+    assert bool((p == 0.5).all()) and bool((opt.state[0] == 0).all())
+    # and the context still works afterwards
+    assert step(p.data_ptr(), g.data_ptr(), sp) == 0
+    torch.cuda.synchronize()
+    assert not bool((p == 0.5).all())
+    opt.close()
+
+
+def test_context_reused_across_different_tensor_lists_and_streams():
+    import torch
+    import paper_2506_10315_amd as P
+    cfg = Hn.make_cfg("small_fc_lopt")
+    w = W.small_fc_weights(0)
+    res = []
+    for use_side_stream in (False, True):
+        opt = P.LearnedOptimizer(cfg, w, [(64, 256), (33,)])
+        p = [torch.full((64, 256), 0.1, device="cuda:0"), torch.full((1, 33), 0.1, device="cuda:0")]
+        g = [torch.linspace(-1e-3, 1e-3, 64 * 256, device="cuda:0").view(64, 256).contiguous(),
+             torch.linspace(-1e-3, 1e-3, 33, device="cuda:0").view(1, 33).contiguous()]
+        torch.cuda.synchronize()
+        if use_side_stream:
+            s = torch.cuda.Stream()
+            with torch.cuda.stream(s):
+                opt.step(p, g)
+                opt.step(p, g)
+            s.synchronize()
+        else:
+            opt.step(p, g)
+            opt.step(p, g)
+        torch.cuda.synchronize()
+        res.append([x.cpu().numpy().copy() for x in p])
+        opt.close()
+    for x, y in zip(*res):
+        assert np.array_equal(x, y)

@@ -508,3 +508,17 @@ def test_rel_err_metric():
     rms = math.sqrt(6 / 4)
     assert O.rel_err(a, b) == pytest.approx(1e-3 / rms)
     assert O.rel_err(b, b) == 0.0
+
+
+def test_apply_rows_equals_the_same_rows_of_a_full_step():
+    C = cfg(hidden=4)
+    rng = np.random.default_rng(19)
+    m, n = 11, 6
+    w = rng.standard_normal(39 * 4 + 4 + 16 + 4 + 8 + 2) * 0.3
+    p = rng.standard_normal((m, n)) * 0.02
+    g = rng.standard_normal((m, n)) * 1e-2
+    st = O.init_state(m, n, C)
+    info = {}
+    full = O.tensor_step(p, g, st, w, C, 2, 0.8, 0.02, out=info)
+    part = O.apply_rows(p, g, st, info["stats"], w, C, 2, 0.8, 0.02, slice(3, 7))
+    np.testing.assert_allclose(part, full[3:7], rtol=1e-13)
