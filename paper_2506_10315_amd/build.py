@@ -19,6 +19,7 @@ UNITS = [
     ("lopt_apply_valu.hip", "apply_small_fc", ["-DLOPT_APPLY_KIND=0"]),
     ("lopt_apply_valu.hip", "apply_velo", ["-DLOPT_APPLY_KIND=1"]),
     ("lopt_apply_mfma.hip", "apply_mfma", []),
+    ("lopt_apply_f16.hip", "apply_f16", []),
 ]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

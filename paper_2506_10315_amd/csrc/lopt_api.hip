@@ -80,7 +80,7 @@ struct lopt_ctx {
   size_t h_stage_bytes = 0;
   hipEvent_t stage_ev = nullptr;
   bool stage_pending = false;
-  bool force_valu = false;         // LOPT_FORCE_VALU=1 in the environment at create: skip the MFMA apply kernel
+  int apply_variant = 0;           // 0 auto, 1 vector ALU, 2 fp32 MFMA, 3 split-fp16 MFMA (LOPT_APPLY in the environment at create)
   // optional per-pass timing
   bool profiling = false;
   std::vector<hipEvent_t> prof_events;   // (LOPT_N_PASSES + 1) events per recorded step
@@ -305,7 +305,9 @@ lopt_status lopt_create(const lopt_config* cfg, const float* weights_host, size_
   lopt_ctx* ctx = new (std::nothrow) lopt_ctx();
   if (!ctx) return fail(nullptr, LOPT_ENOMEM, "out of host memory");
   ctx->cfg = *cfg;
-  { const char* e = getenv("LOPT_FORCE_VALU"); ctx->force_valu = e && e[0] == '1'; }
+  if (const char* e = getenv("LOPT_APPLY")) {
+    ctx->apply_variant = !strcmp(e, "valu") ? 1 : !strcmp(e, "mfma_f32") ? 2 : !strcmp(e, "mfma_f16x3") ? 3 : 0;
+  }
   const int H = (int)cfg->hidden;
   ctx->HP = padded_hidden(H);
   ctx->F = cfg->kind == LOPT_SMALL_FC ? LOPT_N_ELEM_FEATS : LOPT_D_VELO;
@@ -327,7 +329,9 @@ lopt_status lopt_create(const lopt_config* cfg, const float* weights_host, size_
   CREATE_TRY(hipEventCreateWithFlags(&ctx->stage_ev, hipEventDisableTiming));
   if (cfg->kind == LOPT_SMALL_FC) {
     const int HP = ctx->HP;
-    std::vector<float> tail((size_t)HP * HP + HP + 2 * HP + 2, 0.f);
+    // W2 b2 W3 b3 zero-padded to HP, followed by the un-normalized first layer W1[28][HP] (padded)
+    const size_t tail_n = (size_t)HP * HP + HP + 2 * HP + 2;
+    std::vector<float> tail(tail_n + 2 + (size_t)LOPT_N_ELEM_FEATS * HP, 0.f);
     const float* W2 = weights_host + (size_t)LOPT_D_SMALL_FC * H + H;
     const float* b2 = W2 + (size_t)H * H;
     const float* W3 = b2 + H;
@@ -338,6 +342,8 @@ lopt_status lopt_create(const lopt_config* cfg, const float* weights_host, size_
     for (int a = 0; a < H; ++a) { tail[(size_t)HP * HP + HP + 2 * a] = W3[2 * a]; tail[(size_t)HP * HP + HP + 2 * a + 1] = W3[2 * a + 1]; }
     tail[(size_t)HP * HP + HP + 2 * HP] = b3[0];
     tail[(size_t)HP * HP + HP + 2 * HP + 1] = b3[1];
+    for (int f = 0; f < LOPT_N_ELEM_FEATS; ++f)
+      for (int u = 0; u < H; ++u) tail[tail_n + 2 + (size_t)f * HP + u] = weights_host[(size_t)f * H + u];
     CREATE_TRY(hipMalloc((void**)&ctx->d_tail, tail.size() * sizeof(float)));
     CREATE_TRY(hipMemcpy(ctx->d_tail, tail.data(), tail.size() * sizeof(float), hipMemcpyHostToDevice));
     ctx->W.mlp = ctx->d_weights;
@@ -495,7 +501,9 @@ lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, fl
     MARK(5);
     MARK(6);
   }
-  if (!ctx->force_valu && apply_mfma_available(A)) launch_apply_mfma(L, A, ctx->W, stream);
+  const bool mfma_ok = apply_mfma_available(A);
+  if (mfma_ok && (ctx->apply_variant == 0 || ctx->apply_variant == 3)) launch_apply_f16x3(L, A, ctx->W, stream);
+  else if (mfma_ok && ctx->apply_variant == 2) launch_apply_mfma(L, A, ctx->W, stream);
   else if (ctx->cfg.kind == LOPT_SMALL_FC) launch_apply_small_fc(L, A, ctx->W, stream);
   else launch_apply_velo(L, A, ctx->W, stream);
   MARK(7);

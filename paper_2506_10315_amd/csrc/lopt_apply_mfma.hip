@@ -17,40 +17,32 @@
 //     u(v, half) = 8*(v/4) + 4*half + (v%4), half = l >> 5, in accumulator register v. Register v
 //     (after ReLU) is therefore directly the B operand of layer 2's step v with k_a = u(v,0),
 //     k_b = u(v,1); the A operands (weights) are loaded in that order once per tile.
-//   * Biases enter as the C operand of the first MFMA of each chain.
+//   * Only the 16 features that vary per element go through layer 1's MFMAs (8 steps). The 12
+//     features that are constant along a row or a column contribute a 32-vector per row and a
+//     32-vector per column; with the bias they form the C operand of the first MFMA of the chain
+//     (column vectors are computed once per tile into LDS, laid out so that each ds_read_b128 is
+//     conflict-free; row vectors once per row). Layer 2's bias is the C operand of its first MFMA.
 //   * Layer 3: each lane holds half of its element's hidden units; the two partial dot products
 //     are exchanged with one more v_permlane32_swap.
-#include "lopt_internal.h"
-#include "lopt_device.h"
+#include "lopt_apply_common.h"
 
 namespace lopt {
-
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
-__device__ __forceinline__ void swap32(float& a, float& b) {
-  // v_permlane32_swap: a.hi <-> b.lo, i.e. afterwards a = [a.lo | b.lo], b = [a.hi | b.hi]
-  // (lo = lanes 0..31). Written as inline assembly because the compiler's builtin returns the first
-  // result twice (checked on ROCm 7.2); the s_nop pairs cover the VALU <-> permlane-swap wait states
-  // that the compiler cannot see inside an asm block.
-  asm("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
-}
-
-__device__ __forceinline__ int unit_of(int v, int half) { return 8 * (v >> 2) + 4 * half + (v & 3); }
-
-constexpr int kNF = LOPT_N_ELEM_FEATS;  // 28
-constexpr int kH = 32;
 
 template <bool VEC>
 __device__ __forceinline__ void apply_mfma_tile(const TensorDev& T, const TileDev& tile, const float* __restrict__ ws,
                                                 const StepArgs& A, const float* __restrict__ tail,
-                                                const float* __restrict__ w3s) {
+                                                ApplyLds& L) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int half = lane >> 5, l32 = lane & 31;
   const float* __restrict__ prep = ws + T.oPrep;  // W1s[28][32] (normalization folded in), b1'[32]
-  float a1[kNF / 2], a2[kH / 2];
+  const int n = T.n, m = T.m;
+
+  apply_tile_setup(T, tile, ws, prep, tail, L);
+
+  float a1[kNE / 2], a2[kH / 2];
   f32x16 cb1, cb2;
 #pragma unroll
-  for (int s = 0; s < kNF / 2; ++s) a1[s] = prep[(2 * s + half) * kH + l32];
+  for (int s = 0; s < kNE / 2; ++s) a1[s] = prep[(half ? elem_feat(2 * s + 1) : elem_feat(2 * s)) * kH + l32];
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
     const int u = unit_of(v, half);
@@ -59,83 +51,86 @@ __device__ __forceinline__ void apply_mfma_tile(const TensorDev& T, const TileDe
     cb2[v] = tail[kH * kH + u];
   }
   const float b3d = tail[kH * kH + kH + 2 * kH], b3m = tail[kH * kH + kH + 2 * kH + 1];
-  const float4* __restrict__ w3 = reinterpret_cast<const float4*>(w3s) + half * 8;  // [v/2]: d(v) m(v) d(v+1) m(v+1)
 
-  const int n = T.n, m = T.m;
   const int col = tile.tj * kTileCols + 4 * lane;
   const int r0 = tile.ti * T.TR;
   const int r1 = min(r0 + T.TR, m);
-  float4 rc[3], cc[3];
-  const float* cst = T.st + 4 * (size_t)T.padN + 3 * (size_t)T.padm;
+  float4 rc[3];
 #pragma unroll
-  for (int k = 0; k < 3; ++k) {
-    rc[k] = load4<VEC>(ws + T.oRC + (size_t)k * T.padn, col, n);
-    cc[k] = load4<VEC>(cst + (size_t)k * T.padn, col, n);
-  }
-  const float* __restrict__ M1 = T.st;
-  const float* __restrict__ M2 = T.st + (size_t)T.padN;
-  const float* __restrict__ M3 = T.st + 2 * (size_t)T.padN;
-  const float* __restrict__ Vp = T.st + 3 * (size_t)T.padN;
+  for (int k = 0; k < 3; ++k) rc[k] = load4<VEC>(ws + T.oRC + (size_t)k * T.padn, col, n);
   const float* rst = T.st + 4 * (size_t)T.padN;
   const float eps = A.eps_acc, lr = A.lr, wd = A.wd;
-  const float zero = 0.f;
 
-  for (int r = r0 + wave; r < r1; r += 4) {
+  int r = r0 + wave;
+  float4 cur[6];
+  if (r < r1) load_row<VEC>(T, (size_t)r * n, col, n, cur);
+  for (; r < r1; r += 4) {
     const size_t ro = (size_t)r * n;
-    const float4 g4 = load4<VEC>(T.g + ro, col, n);
-    const float4 p4 = load4<VEC>(T.p + ro, col, n);
-    const float4 m1 = load4<VEC>(M1 + ro, col, n);
-    const float4 m2 = load4<VEC>(M2 + ro, col, n);
-    const float4 m3 = load4<VEC>(M3 + ro, col, n);
-    const float4 v4 = load4<VEC>(Vp + ro, col, n);
+    float4 nxt[6];
+    if (r + 4 < r1) load_row<VEC>(T, (size_t)(r + 4) * n, col, n, nxt);   // next row in flight during the MLP
     float rr[3], rv[3];
 #pragma unroll
     for (int k = 0; k < 3; ++k) {
       rr[k] = ws[T.oRR + (size_t)k * T.padm + r];
       rv[k] = rst[(size_t)k * T.padm + r];
     }
+    // bias + row-constant features for this row, for the lane's 16 hidden units
+    f32x16 cbr = cb1;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+#pragma unroll
+      for (int f = 0; f < 6; ++f) {
+        const float4 w = L.w1row[f][half][q];
+        const float xf = f < 3 ? rv[f] : rr[f - 3];
+        cbr[4 * q] += xf * w.x; cbr[4 * q + 1] += xf * w.y; cbr[4 * q + 2] += xf * w.z; cbr[4 * q + 3] += xf * w.w;
+      }
+    }
     float pn[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      float x[kNF];
+      float x[kNE];
       {
-        const float g = get(g4, e), p = get(p4, e);
-        const float q1 = get(m1, e), q2 = get(m2, e), q3 = get(m3, e), v = get(v4, e);
+        const float g = get(cur[0], e);
+        const float q1 = get(cur[2], e), q2 = get(cur[3], e), q3 = get(cur[4], e), v = get(cur[5], e);
         const float rs = rsqrtf(v + eps);
-        const float c0 = get(rc[0], e), c1 = get(rc[1], e), c2 = get(rc[2], e);
-        const float f0 = rr[0] * c0, f1 = rr[1] * c1, f2 = rr[2] * c2;
-        x[0] = g; x[1] = p; x[2] = q1; x[3] = q2; x[4] = q3; x[5] = v;
+        const float f0 = rr[0] * get(rc[0], e), f1 = rr[1] * get(rc[1], e), f2 = rr[2] * get(rc[2], e);
+        x[0] = g; x[1] = get(cur[1], e); x[2] = q1; x[3] = q2; x[4] = q3; x[5] = v;
         x[6] = q1 * rs; x[7] = q2 * rs; x[8] = q3 * rs; x[9] = rs;
         x[10] = g * f0; x[11] = g * f1; x[12] = g * f2;
-        x[13] = rv[0]; x[14] = rv[1]; x[15] = rv[2];
-        x[16] = get(cc[0], e); x[17] = get(cc[1], e); x[18] = get(cc[2], e);
-        x[19] = rr[0]; x[20] = rr[1]; x[21] = rr[2];
-        x[22] = c0; x[23] = c1; x[24] = c2;
-        x[25] = q1 * f0; x[26] = q2 * f1; x[27] = q3 * f2;
+        x[13] = q1 * f0; x[14] = q2 * f1; x[15] = q3 * f2;
       }
       // x[2s] -> B operand of step s for tile E1, x[2s+1] -> for tile E2
 #pragma unroll
-      for (int s = 0; s < kNF / 2; ++s) swap32(x[2 * s], x[2 * s + 1]);
-      f32x16 h1a = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[0], x[0], cb1, 0, 0, 0);
-      f32x16 h1b = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[0], x[1], cb1, 0, 0, 0);
+      for (int s = 0; s < kNE / 2; ++s) swap32(x[2 * s], x[2 * s + 1]);
+      // C operand of layer 1: bias + row vector + column vector of the tile's element
+      f32x16 h1a, h1b;
 #pragma unroll
-      for (int s = 1; s < kNF / 2; ++s) {
+      for (int q = 0; q < 4; ++q) {
+        const float4 ca = L.colv[q][half][e][l32];
+        const float4 cb = L.colv[q][half][e][32 + l32];
+        h1a[4 * q] = cbr[4 * q] + ca.x; h1a[4 * q + 1] = cbr[4 * q + 1] + ca.y;
+        h1a[4 * q + 2] = cbr[4 * q + 2] + ca.z; h1a[4 * q + 3] = cbr[4 * q + 3] + ca.w;
+        h1b[4 * q] = cbr[4 * q] + cb.x; h1b[4 * q + 1] = cbr[4 * q + 1] + cb.y;
+        h1b[4 * q + 2] = cbr[4 * q + 2] + cb.z; h1b[4 * q + 3] = cbr[4 * q + 3] + cb.w;
+      }
+#pragma unroll
+      for (int s = 0; s < kNE / 2; ++s) {
         h1a = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[s], x[2 * s], h1a, 0, 0, 0);
         h1b = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[s], x[2 * s + 1], h1b, 0, 0, 0);
       }
-      f32x16 h2a = __builtin_amdgcn_mfma_f32_32x32x2f32(a2[0], fmaxf(h1a[0], zero), cb2, 0, 0, 0);
-      f32x16 h2b = __builtin_amdgcn_mfma_f32_32x32x2f32(a2[0], fmaxf(h1b[0], zero), cb2, 0, 0, 0);
+      f32x16 h2a = __builtin_amdgcn_mfma_f32_32x32x2f32(a2[0], relu(h1a[0]), cb2, 0, 0, 0);
+      f32x16 h2b = __builtin_amdgcn_mfma_f32_32x32x2f32(a2[0], relu(h1b[0]), cb2, 0, 0, 0);
 #pragma unroll
       for (int v = 1; v < 16; ++v) {
-        h2a = __builtin_amdgcn_mfma_f32_32x32x2f32(a2[v], fmaxf(h1a[v], zero), h2a, 0, 0, 0);
-        h2b = __builtin_amdgcn_mfma_f32_32x32x2f32(a2[v], fmaxf(h1b[v], zero), h2b, 0, 0, 0);
+        h2a = __builtin_amdgcn_mfma_f32_32x32x2f32(a2[v], relu(h1a[v]), h2a, 0, 0, 0);
+        h2b = __builtin_amdgcn_mfma_f32_32x32x2f32(a2[v], relu(h1b[v]), h2b, 0, 0, 0);
       }
       float da = 0.f, ma = 0.f, db = 0.f, mb = 0.f;
 #pragma unroll
       for (int v2 = 0; v2 < 8; ++v2) {
-        const float4 w = w3[v2];
-        const float ha0 = fmaxf(h2a[2 * v2], zero), ha1 = fmaxf(h2a[2 * v2 + 1], zero);
-        const float hb0 = fmaxf(h2b[2 * v2], zero), hb1 = fmaxf(h2b[2 * v2 + 1], zero);
+        const float4 w = L.w3[half][v2];
+        const float ha0 = relu(h2a[2 * v2]), ha1 = relu(h2a[2 * v2 + 1]);
+        const float hb0 = relu(h2b[2 * v2]), hb1 = relu(h2b[2 * v2 + 1]);
         da += ha0 * w.x; ma += ha0 * w.y; da += ha1 * w.z; ma += ha1 * w.w;
         db += hb0 * w.x; mb += hb0 * w.y; db += hb1 * w.z; mb += hb1 * w.w;
       }
@@ -143,27 +138,24 @@ __device__ __forceinline__ void apply_mfma_tile(const TensorDev& T, const TileDe
       swap32(ma, mb);
       const float d = (da + db) + b3d, mg = (ma + mb) + b3m;
       const float delta = d * expf(mg * A.exp_mult) * A.step_mult;
-      const float p = get(p4, e);
+      const float p = get(cur[1], e);
       pn[e] = p - lr * (delta + wd * p);
+      __builtin_amdgcn_sched_barrier(0);   // keep the four rounds apart: bounds register pressure
     }
     store4<VEC>(T.p + ro, col, n, make_float4(pn[0], pn[1], pn[2], pn[3]));
+#pragma unroll
+    for (int i = 0; i < 6; ++i) cur[i] = nxt[i];
   }
 }
 
 __global__ void __launch_bounds__(kBlock, 2) k_apply_mfma(const TensorDev* __restrict__ tensors,
                                                           const TileDev* __restrict__ tiles, float* __restrict__ ws,
                                                           StepArgs A, const float* __restrict__ tail) {
-  // W3 per half-wave: w3s[half][v][2] = W3[unit_of(v, half)][0..1]
-  __shared__ __attribute__((aligned(16))) float w3s[2 * 16 * 2];
-  if (threadIdx.x < 64) {
-    const int half = threadIdx.x >> 5, v = (threadIdx.x >> 1) & 15, j = threadIdx.x & 1;
-    w3s[threadIdx.x] = tail[kH * kH + kH + 2 * unit_of(v, half) + j];
-  }
-  __syncthreads();
+  __shared__ ApplyLds L;
   const TileDev tile = tiles[blockIdx.x];
   const TensorDev& T = tensors[tile.tensor];
-  if (T.vec) apply_mfma_tile<true>(T, tile, ws, A, tail, w3s);
-  else apply_mfma_tile<false>(T, tile, ws, A, tail, w3s);
+  if (T.vec) apply_mfma_tile<true>(T, tile, ws, A, tail, L);
+  else apply_mfma_tile<false>(T, tile, ws, A, tail, L);
 }
 
 bool apply_mfma_available(const StepArgs& A) { return A.kind == LOPT_SMALL_FC && A.HP == kH; }

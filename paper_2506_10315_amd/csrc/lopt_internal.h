@@ -64,7 +64,7 @@ struct StepArgs {
 struct WeightsDev {
   // small_fc_lopt (original layout, as uploaded)
   const float* mlp;    // W1[39,H] b1[H] W2[H,H] b2[H] W3[H,2] b3[2]
-  const float* mlp_tail;  // W2[HP,HP] b2[HP] W3[HP,2] b3[2], zero-padded to the padded width HP
+  const float* mlp_tail;  // W2[HP,HP] b2[HP] W3[HP,2] b3[2] pad[2] W1[28,HP]: zero-padded to the padded width HP
   // VeLO
   const float* Wx; const float* Wh; const float* b; const float* Wa; const float* ba; const float* B;
 };
@@ -91,5 +91,6 @@ void launch_apply_small_fc(const Launch&, const StepArgs&, const WeightsDev&, hi
 void launch_apply_velo(const Launch&, const StepArgs&, const WeightsDev&, hipStream_t);
 bool apply_mfma_available(const StepArgs&);
 void launch_apply_mfma(const Launch&, const StepArgs&, const WeightsDev&, hipStream_t);
+void launch_apply_f16x3(const Launch&, const StepArgs&, const WeightsDev&, hipStream_t);
 
 }  // namespace lopt
