@@ -21,8 +21,8 @@ if ROOT not in sys.path:
 import numpy as np
 
 HBM_PEAK_GBS = 8000.0
-MFMA_F32_PEAK_TFLOPS = 157.3
-VALU_F32_PEAK_TFLOPS = 157.3
+MFMA_F32_PEAK_TFLOPS = 157.3      # fp32 matrix (= packed fp32 vector) peak
+MFMA_F16_PEAK_TFLOPS = 2500.0     # dense fp16/bf16 matrix peak
 
 # Algorithmic work per element of the dominant pass:
 #   apply pass, small_fc_lopt hidden 32: MLP contraction 28*32 + 32*32 + 32*2 MACs = 3968 FLOP
@@ -128,17 +128,29 @@ def main():
 
     dominant = max(pass_ms, key=pass_ms.get)
     dur_s = pass_ms[dominant] * 1e-3
-    if dominant == "apply" and optimizer == "small_fc_lopt":
-        bound, unit, peak = "mfma", "TFLOP/s", MFMA_F32_PEAK_TFLOPS
+    variant = os.environ.get("LOPT_APPLY", "auto")
+    if dominant == "apply" and optimizer == "small_fc_lopt" and variant != "valu":
+        # the MLP contraction runs on the matrix cores: fp32 MFMA (variant mfma_f32) or three fp16 MFMA terms
+        # per product (default); either way the algorithmic work is the fp32 contraction of the paper's MLP
+        f16 = variant in ("auto", "mfma_f16x3")
+        bound, unit = "mfma", "TFLOP/s"
+        peak = MFMA_F16_PEAK_TFLOPS if f16 else MFMA_F32_PEAK_TFLOPS
         achieved = APPLY_FLOP_SMALL_FC * n_el / dur_s / 1e12
+        kernel = "apply (k_apply_f16x3: fp16 hi+lo operands, 3 MFMA terms, fp32 accumulate)" if f16 else \
+                 "apply (k_apply_mfma: fp32 MFMA)"
     else:
         bound, unit, peak = "hbm", "GB/s", HBM_PEAK_GBS
         per = APPLY_BYTES if dominant == "apply" else ACCUM_BYTES if dominant == "accum_stats" else 4
         achieved = per * n_el / dur_s / 1e9
-    roofline = {"bound": bound, "kernel": dominant, "achieved": achieved, "peak": peak, "unit": unit,
+        kernel = dominant
+    roofline = {"bound": bound, "kernel": kernel, "achieved": achieved, "peak": peak, "unit": unit,
                 "frac": achieved / peak, "traffic": None,
                 "avg_launch_ms": pass_ms[dominant], "pass_ms": pass_ms,
                 "ms_per_step_with_events": dt_prof / args.steps * 1e3}
+    # every HBM-bound pass against the 8 TB/s roof (algorithmic bytes per element: 4 / 40 / 28)
+    roofline["hbm_frac_by_pass"] = {
+        name: (b * n_el / (pass_ms[name] * 1e-3) / 1e9) / HBM_PEAK_GBS
+        for name, b in (("rowcol_sums", 4), ("accum_stats", ACCUM_BYTES), ("apply", APPLY_BYTES)) if pass_ms[name] > 0}
     out = {
         "metric": "optimizer-step throughput", "value": n_el / (dt / args.steps) / 1e9, "unit": "Gparams/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,

@@ -14,6 +14,23 @@ __device__ __forceinline__ void swap32(unsigned& a, unsigned& b) {
   asm("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
 }
 
+// Eight swaps (register i with register 4+i of both arrays) and two swaps as single asm blocks: the
+// wait states are needed only before the first and after the last swap of a block, and every
+// s_nop costs an issue slot.
+__device__ __forceinline__ void swap32x8(unsigned (&h)[8], unsigned (&l)[8]) {
+  asm("s_nop 1\n\tv_permlane32_swap_b32 %0, %4\n\tv_permlane32_swap_b32 %1, %5\n\t"
+      "v_permlane32_swap_b32 %2, %6\n\tv_permlane32_swap_b32 %3, %7\n\t"
+      "v_permlane32_swap_b32 %8, %12\n\tv_permlane32_swap_b32 %9, %13\n\t"
+      "v_permlane32_swap_b32 %10, %14\n\tv_permlane32_swap_b32 %11, %15\n\ts_nop 1"
+      : "+v"(h[0]), "+v"(h[1]), "+v"(h[2]), "+v"(h[3]), "+v"(h[4]), "+v"(h[5]), "+v"(h[6]), "+v"(h[7]),
+        "+v"(l[0]), "+v"(l[1]), "+v"(l[2]), "+v"(l[3]), "+v"(l[4]), "+v"(l[5]), "+v"(l[6]), "+v"(l[7]));
+}
+
+__device__ __forceinline__ void swap32x2(float& a0, float& b0, float& a1, float& b1) {
+  asm("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\tv_permlane32_swap_b32 %2, %3\n\ts_nop 1"
+      : "+v"(a0), "+v"(b0), "+v"(a1), "+v"(b1));
+}
+
 __device__ __forceinline__ void swap32(float& a, float& b) {
   // v_permlane32_swap: a.hi <-> b.lo, i.e. afterwards a = [a.lo | b.lo], b = [a.hi | b.hi]
   // (lo = lanes 0..31). Written as inline assembly because the compiler's builtin returns the first

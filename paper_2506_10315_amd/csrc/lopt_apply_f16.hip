@@ -36,13 +36,15 @@ __device__ __forceinline__ f16x8 as_f16x8(unsigned a, unsigned b, unsigned c, un
   return __builtin_bit_cast(f16x8, v);
 }
 
-// (a, b) -> packed hi pair and packed lo pair, hi = rtz_fp16(x), lo = rtz_fp16(x - hi)
+// (a, b) -> packed hi pair and packed lo pair, hi = rtz_fp16(x), lo = rtz_fp16(x - hi).
+// The residual x - float(hi) is one mixed-precision FMA (v_fma_mix_f32 reads the fp16 half directly):
+// the compiler only forms it when x itself is a product, so it is written out here.
 __device__ __forceinline__ void split2(float a, float b, unsigned& hi, unsigned& lo) {
-  const auto h = __builtin_amdgcn_cvt_pkrtz(a, b);
-  const float ra = a - (float)h[0], rb = b - (float)h[1];
-  const auto l = __builtin_amdgcn_cvt_pkrtz(ra, rb);
-  hi = __builtin_bit_cast(unsigned, h);
-  lo = __builtin_bit_cast(unsigned, l);
+  hi = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(a, b));
+  float ra, rb;
+  asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel_hi:[1,0,0]" : "=v"(ra) : "v"(hi), "v"(a));
+  asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(rb) : "v"(hi), "v"(b));
+  lo = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(ra, rb));
 }
 
 __device__ __forceinline__ f32x16 mfma3(const f16x8& ah, const f16x8& al, const f16x8& bh, const f16x8& bl,
@@ -98,13 +100,17 @@ __device__ __forceinline__ void apply_f16_tile(const TensorDev& T, const TileDev
       a2l[j] = as_f16x8(pl[0], pl[1], pl[2], pl[3]);
     }
   }
-  f32x16 cb1, cb2;
+  f32x16 cb2;
 #pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    const int u = unit_of(v, half);
-    cb1[v] = prep[kNF * kH + u];
-    cb2[v] = tail[kH * kH + u];
-  }
+  for (int v = 0; v < 16; ++v) cb2[v] = tail[kH * kH + unit_of(v, half)];
+  // Row part of layer 1's C operand (bias + the six row-constant features): one value per hidden
+  // unit and row, injected through the matrix engine as k slot 0 of an extra MFMA against a constant
+  // B operand that is 1 in that slot. Lane l < 32 carries unit l.
+  float w1r[6];
+#pragma unroll
+  for (int f = 0; f < 6; ++f) w1r[f] = prep[row_feat(f) * kH + l32];
+  const float b1l = prep[kNF * kH + l32];
+  const f16x8 b_one = as_f16x8(half ? 0u : 0x3C00u, 0u, 0u, 0u);   // fp16 1.0 in k slot 0
   const float b3d = tail[kH * kH + kH + 2 * kH], b3m = tail[kH * kH + kH + 2 * kH + 1];
   float sc[kNE];  // normalization factors of the per-element features (wave-uniform)
 #pragma unroll
@@ -132,16 +138,16 @@ __device__ __forceinline__ void apply_f16_tile(const TensorDev& T, const TileDev
       rr[k] = ws[T.oRR + (size_t)k * T.padm + r];
       rv[k] = rst[(size_t)k * T.padm + r];
     }
-    // bias + row-constant features for this row, for the lane's 16 hidden units
-    f32x16 cbr = cb1;
+    // bias + row-constant features of this row for hidden unit (lane & 31), split into fp16 hi + lo
+    f16x8 rbh, rbl;
+    {
+      float rb = b1l;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-#pragma unroll
-      for (int f = 0; f < 6; ++f) {
-        const float4 w = L.w1row[f][half][q];
-        const float xf = f < 3 ? rv[f] : rr[f - 3];
-        cbr[4 * q] += xf * w.x; cbr[4 * q + 1] += xf * w.y; cbr[4 * q + 2] += xf * w.z; cbr[4 * q + 3] += xf * w.w;
-      }
+      for (int f = 0; f < 6; ++f) rb += (f < 3 ? rv[f] : rr[f - 3]) * w1r[f];
+      unsigned h, l;
+      split2(half ? 0.f : rb, 0.f, h, l);
+      rbh = as_f16x8(h, 0u, 0u, 0u);
+      rbl = as_f16x8(l, 0u, 0u, 0u);
     }
     float pn[4];
 #pragma unroll
@@ -161,19 +167,21 @@ __device__ __forceinline__ void apply_f16_tile(const TensorDev& T, const TileDev
         for (int i = 0; i < 8; ++i) split2(x[2 * i] * sc[2 * i], x[2 * i + 1] * sc[2 * i + 1], ph[i], pl[i]);
       }
       // registers 0..3 -> B operand of tile E1, registers 4..7 -> B operand of tile E2
-#pragma unroll
-      for (int i = 0; i < 4; ++i) { swap32(ph[i], ph[4 + i]); swap32(pl[i], pl[4 + i]); }
-      // C operand of layer 1: bias + row vector + column vector of the tile's element
+      swap32x8(ph, pl);
+      // C operand of layer 1: the column vector of the tile's element straight from LDS; the row part
+      // (bias + row-constant features) comes in through two extra MFMAs
       f32x16 h1a, h1b;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const float4 ca = L.colv[q][half][e][l32];
         const float4 cb = L.colv[q][half][e][32 + l32];
-        h1a[4 * q] = cbr[4 * q] + ca.x; h1a[4 * q + 1] = cbr[4 * q + 1] + ca.y;
-        h1a[4 * q + 2] = cbr[4 * q + 2] + ca.z; h1a[4 * q + 3] = cbr[4 * q + 3] + ca.w;
-        h1b[4 * q] = cbr[4 * q] + cb.x; h1b[4 * q + 1] = cbr[4 * q + 1] + cb.y;
-        h1b[4 * q + 2] = cbr[4 * q + 2] + cb.z; h1b[4 * q + 3] = cbr[4 * q + 3] + cb.w;
+        h1a[4 * q] = ca.x; h1a[4 * q + 1] = ca.y; h1a[4 * q + 2] = ca.z; h1a[4 * q + 3] = ca.w;
+        h1b[4 * q] = cb.x; h1b[4 * q + 1] = cb.y; h1b[4 * q + 2] = cb.z; h1b[4 * q + 3] = cb.w;
       }
+      h1a = __builtin_amdgcn_mfma_f32_32x32x16_f16(rbl, b_one, h1a, 0, 0, 0);
+      h1b = __builtin_amdgcn_mfma_f32_32x32x16_f16(rbl, b_one, h1b, 0, 0, 0);
+      h1a = __builtin_amdgcn_mfma_f32_32x32x16_f16(rbh, b_one, h1a, 0, 0, 0);
+      h1b = __builtin_amdgcn_mfma_f32_32x32x16_f16(rbh, b_one, h1b, 0, 0, 0);
       h1a = mfma3(a1h, a1l, as_f16x8(ph[0], ph[1], ph[2], ph[3]), as_f16x8(pl[0], pl[1], pl[2], pl[3]), h1a);
       h1b = mfma3(a1h, a1l, as_f16x8(ph[4], ph[5], ph[6], ph[7]), as_f16x8(pl[4], pl[5], pl[6], pl[7]), h1b);
       f32x16 h2a = cb2, h2b = cb2;
@@ -194,8 +202,7 @@ __device__ __forceinline__ void apply_f16_tile(const TensorDev& T, const TileDev
         da += ha0 * w.x; ma += ha0 * w.y; da += ha1 * w.z; ma += ha1 * w.w;
         db += hb0 * w.x; mb += hb0 * w.y; db += hb1 * w.z; mb += hb1 * w.w;
       }
-      swap32(da, db);
-      swap32(ma, mb);
+      swap32x2(da, db, ma, mb);
       const float d = (da + db) + b3d, mg = (ma + mb) + b3m;
       const float delta = d * expf(mg * A.exp_mult) * A.step_mult;
       const float p = get(cur[1], e);
