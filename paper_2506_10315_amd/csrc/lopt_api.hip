@@ -505,6 +505,7 @@ lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, fl
   if (mfma_ok && (ctx->apply_variant == 0 || ctx->apply_variant == 3)) launch_apply_f16x3(L, A, ctx->W, stream);
   else if (mfma_ok && ctx->apply_variant == 2) launch_apply_mfma(L, A, ctx->W, stream);
   else if (ctx->cfg.kind == LOPT_SMALL_FC) launch_apply_small_fc(L, A, ctx->W, stream);
+  else if (ctx->apply_variant != 1 && apply_velo4_available(A)) launch_apply_velo4(L, A, stream);
   else launch_apply_velo(L, A, ctx->W, stream);
   MARK(7);
 #undef MARK

@@ -91,6 +91,8 @@ void launch_apply_small_fc(const Launch&, const StepArgs&, const WeightsDev&, hi
 void launch_apply_velo(const Launch&, const StepArgs&, const WeightsDev&, hipStream_t);
 bool apply_mfma_available(const StepArgs&);
 void launch_apply_mfma(const Launch&, const StepArgs&, const WeightsDev&, hipStream_t);
+bool apply_velo4_available(const StepArgs&);
+void launch_apply_velo4(const Launch&, const StepArgs&, hipStream_t);
 void launch_apply_f16x3(const Launch&, const StepArgs&, const WeightsDev&, hipStream_t);
 
 }  // namespace lopt

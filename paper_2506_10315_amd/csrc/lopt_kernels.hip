@@ -378,22 +378,26 @@ void launch_finalize(const Launch& L, const StepArgs& A, const WeightsDev& W, fl
 
 // ----------------------------------------------------------------------------- VeLO hypernetwork
 
-// One LSTM-cell step for a group of tensors. Workgroup = (group of kLstmTensorsPerBlock tensors,
-// slab of 64 hidden units); thread = (unit, quarter of the tensors' inputs is not split: each thread
-// owns one unit for all tensors of the group and computes its four gates).
-__global__ void __launch_bounds__(kWave) k_velo_lstm(const TensorDev* __restrict__ tensors, StepArgs A, WeightsDev W,
-                                                     const float* __restrict__ lstm_u, float* __restrict__ h_new) {
-  extern __shared__ float sh[];  // [kLstmTensorsPerBlock][kLstmInPad + HL]
+// One LSTM-cell step for a group of kLstmTensorsPerBlock tensors and a slab of kLstmUnits hidden units.
+// A workgroup's 64 gate columns are (gate g = lane / 16, unit u0 + lane % 16); the reduction over the
+// 45 + H_L inputs is split across the workgroup's wavefronts (8 or 16) and finished through LDS, then one thread
+// per (tensor, unit) applies the cell equations. Inputs u and the previous h sit in LDS.
+constexpr int kLstmUnits = 16;
+
+__global__ void __launch_bounds__(1024) k_velo_lstm(const TensorDev* __restrict__ tensors, StepArgs A, WeightsDev W,
+                                                      const float* __restrict__ lstm_u, float* __restrict__ h_new) {
+  extern __shared__ float sh[];  // x[kLstmTensorsPerBlock][kLstmInPad + HLp] then zpart[nw][kLstmTensorsPerBlock][64]
   const int HL = A.HL;
-  const int stride = kLstmInPad + HL;
+  const int stride = kLstmInPad + ((HL + 3) & ~3);
+  float* zpart = sh + kLstmTensorsPerBlock * stride;
   const int t0 = blockIdx.x * kLstmTensorsPerBlock;
   const int nt = min(kLstmTensorsPerBlock, A.n_tensors - t0);
-  for (int i = threadIdx.x; i < kLstmTensorsPerBlock * stride; i += kWave) {
+  for (int i = threadIdx.x; i < kLstmTensorsPerBlock * stride; i += blockDim.x) {
     const int tt = i / stride, k = i - tt * stride;
     float v = 0.f;
     if (tt < nt) {
       if (k < kLstmInPad) v = lstm_u[(size_t)(t0 + tt) * kLstmInPad + k];
-      else {
+      else if (k - kLstmInPad < HL) {
         const TensorDev& T = tensors[t0 + tt];
         v = T.st[4 * (size_t)T.padN + 3 * (size_t)T.padm + 3 * (size_t)T.padn + (k - kLstmInPad)];
       }
@@ -401,50 +405,60 @@ __global__ void __launch_bounds__(kWave) k_velo_lstm(const TensorDev* __restrict
     sh[i] = v;
   }
   __syncthreads();
-  const int u = blockIdx.y * kWave + threadIdx.x;
-  if (u >= HL) return;
-  float z[4][kLstmTensorsPerBlock];
-#pragma unroll
-  for (int gI = 0; gI < 4; ++gI) {
-    const float bb = W.b[gI * HL + u];
-#pragma unroll
-    for (int tt = 0; tt < kLstmTensorsPerBlock; ++tt) z[gI][tt] = bb;
-  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  const int gI = lane >> 4, u = blockIdx.y * kLstmUnits + (lane & 15);
+  const bool live = u < HL;
   const int G = 4 * HL;
-  for (int k = 0; k < LOPT_VELO_LSTM_IN; ++k) {
+  const size_t colw = (size_t)gI * HL + (live ? u : 0);
+  float z[kLstmTensorsPerBlock];
+#pragma unroll
+  for (int tt = 0; tt < kLstmTensorsPerBlock; ++tt) z[tt] = 0.f;
+  // rows of [Wx ; Wh] handled by this wavefront: w, w+nw, ...; four rows (independent loads) per trip
+  const int nrows = LOPT_VELO_LSTM_IN + HL;
+  for (int kb = wave; kb < nrows; kb += 4 * nw) {
     float w[4];
+    int kk[4];
 #pragma unroll
-    for (int gI = 0; gI < 4; ++gI) w[gI] = W.Wx[(size_t)k * G + gI * HL + u];
+    for (int j = 0; j < 4; ++j) {
+      const int k = kb + nw * j;
+      kk[j] = k;
+      w[j] = 0.f;
+      if (k < nrows && live)
+        w[j] = k < LOPT_VELO_LSTM_IN ? W.Wx[(size_t)k * G + colw] : W.Wh[(size_t)(k - LOPT_VELO_LSTM_IN) * G + colw];
+    }
 #pragma unroll
-    for (int tt = 0; tt < kLstmTensorsPerBlock; ++tt) {
-      const float x = sh[tt * stride + k];
+    for (int j = 0; j < 4; ++j) {
+      if (kk[j] < nrows) {
+        const int xi = kk[j] < LOPT_VELO_LSTM_IN ? kk[j] : kLstmInPad + (kk[j] - LOPT_VELO_LSTM_IN);
 #pragma unroll
-      for (int gI = 0; gI < 4; ++gI) z[gI][tt] += x * w[gI];
+        for (int tt = 0; tt < kLstmTensorsPerBlock; ++tt) z[tt] += sh[tt * stride + xi] * w[j];
+      }
     }
   }
-  for (int k = 0; k < HL; ++k) {
-    float w[4];
 #pragma unroll
-    for (int gI = 0; gI < 4; ++gI) w[gI] = W.Wh[(size_t)k * G + gI * HL + u];
+  for (int tt = 0; tt < kLstmTensorsPerBlock; ++tt) zpart[(wave * kLstmTensorsPerBlock + tt) * 64 + lane] = z[tt];
+  __syncthreads();
+  if (threadIdx.x < kLstmTensorsPerBlock * kLstmUnits) {
+    const int tt = threadIdx.x / kLstmUnits, uu = threadIdx.x % kLstmUnits;
+    const int unit = blockIdx.y * kLstmUnits + uu;
+    if (tt < nt && unit < HL) {
+      float zz[4];
 #pragma unroll
-    for (int tt = 0; tt < kLstmTensorsPerBlock; ++tt) {
-      const float x = sh[tt * stride + kLstmInPad + k];
-#pragma unroll
-      for (int gI = 0; gI < 4; ++gI) z[gI][tt] += x * w[gI];
-    }
-  }
-#pragma unroll
-  for (int tt = 0; tt < kLstmTensorsPerBlock; ++tt) {
-    if (tt < nt) {
+      for (int g2 = 0; g2 < 4; ++g2) {
+        const int c = g2 * 16 + uu;
+        float a = W.b[g2 * HL + unit];
+        for (int w = 0; w < nw; ++w) a += zpart[(w * kLstmTensorsPerBlock + tt) * 64 + c];
+        zz[g2] = a;
+      }
       const TensorDev& T = tensors[t0 + tt];
       float* cl = T.st + 4 * (size_t)T.padN + 3 * (size_t)T.padm + 3 * (size_t)T.padn + T.padH;
-      const float ig = 1.f / (1.f + expf(-z[0][tt]));
-      const float fg = 1.f / (1.f + expf(-z[1][tt]));
-      const float gg = tanhf(z[2][tt]);
-      const float og = 1.f / (1.f + expf(-z[3][tt]));
-      const float c = fg * cl[u] + ig * gg;
-      cl[u] = c;
-      h_new[(size_t)(t0 + tt) * HL + u] = og * tanhf(c);
+      const float ig = 1.f / (1.f + expf(-zz[0]));
+      const float fg = 1.f / (1.f + expf(-zz[1]));
+      const float gg = tanhf(zz[2]);
+      const float og = 1.f / (1.f + expf(-zz[3]));
+      const float c = fg * cl[unit] + ig * gg;
+      cl[unit] = c;
+      h_new[(size_t)(t0 + tt) * HL + unit] = og * tanhf(c);
     }
   }
 }
@@ -452,42 +466,88 @@ __global__ void __launch_bounds__(kWave) k_velo_lstm(const TensorDev* __restrict
 void launch_velo_lstm(const Launch& L, const StepArgs& A, const WeightsDev& W, const float* lstm_u, float* h_new,
                       hipStream_t s) {
   if (L.n_tensors == 0) return;
-  dim3 grid((L.n_tensors + kLstmTensorsPerBlock - 1) / kLstmTensorsPerBlock, (A.HL + kWave - 1) / kWave);
-  size_t shmem = (size_t)kLstmTensorsPerBlock * (kLstmInPad + A.HL) * sizeof(float);
-  hipLaunchKernelGGL(k_velo_lstm, grid, dim3(kWave), shmem, s, L.tensors, A, W, lstm_u, h_new);
+  dim3 grid((L.n_tensors + kLstmTensorsPerBlock - 1) / kLstmTensorsPerBlock, (A.HL + kLstmUnits - 1) / kLstmUnits);
+  const int stride = kLstmInPad + ((A.HL + 3) & ~3);
+  const int nw = A.HL <= 512 ? 16 : 8;   // wavefronts per workgroup = ways the reduction is split (LDS stays < 64 KB)
+  size_t shmem = (size_t)(kLstmTensorsPerBlock * stride + nw * kLstmTensorsPerBlock * 64) * sizeof(float);
+  hipLaunchKernelGGL(k_velo_lstm, grid, dim3(64 * nw), shmem, s, L.tensors, A, W, lstm_u, h_new);
+}
+
+// Partial matrix-vector product for the hypernetwork head: out[w][c0 + 64 c + lane] = sum over rows
+// k = w, w+nw, ... of x[k] * M[k][col], for the four columns c = 0..3 of this lane. Columns past the
+// end are clamped for the loads (their results are never read); two rows per trip keep eight
+// independent coalesced loads in flight.
+__device__ __forceinline__ void matvec4(const float* __restrict__ x, int n_in, const float* __restrict__ M, int ld,
+                                        int c0, int wave, int nw, int lane, float* __restrict__ part, int W64) {
+  const float* wp[4];
+  float acc0[4], acc1[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const int col = c0 + 64 * c + lane;
+    wp[c] = M + (col < ld ? col : ld - 1);
+    acc0[c] = acc1[c] = 0.f;
+  }
+  int k = wave;
+  for (; k + nw < n_in; k += 2 * nw) {
+    const float x0 = x[k], x1 = x[k + nw];
+    float w0[4], w1[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) { w0[c] = wp[c][(size_t)k * ld]; w1[c] = wp[c][(size_t)(k + nw) * ld]; }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) { acc0[c] += x0 * w0[c]; acc1[c] += x1 * w1[c]; }
+  }
+  if (k < n_in) {
+    const float x0 = x[k];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc0[c] += x0 * wp[c][(size_t)k * ld];
+  }
+#pragma unroll
+  for (int c = 0; c < 4; ++c)
+    if (c0 + 64 * c < W64) part[wave * W64 + c0 + 64 * c + lane] = acc0[c] + acc1[c];
 }
 
 // Head of the hypernetwork for one tensor: alpha = h W_a + b_a, theta = alpha B, written as the
 // prepared (zero-padded, first layer scaled) per-tensor MLP. Also stores the new h into the state.
-__global__ void __launch_bounds__(kBlock) k_velo_head(const TensorDev* __restrict__ tensors, float* __restrict__ ws,
+// Both products split their reduction across the workgroup's wavefronts (combined through LDS in a
+// fixed order); lanes own output columns, so weight reads are coalesced.
+__global__ void __launch_bounds__(1024) k_velo_head(const TensorDev* __restrict__ tensors, float* __restrict__ ws,
                                                       StepArgs A, WeightsDev W, const float* __restrict__ h_new) {
-  extern __shared__ float sh[];  // h[HL] then alpha[K]
+  extern __shared__ float sh[];  // h[HL] | alpha[K] | part[nw][max(K, P) rounded up to 64]
   const TensorDev& T = tensors[blockIdx.x];
-  const int HL = A.HL, K = A.K, H = A.H, HP = A.HP, F = LOPT_D_VELO;
+  const int HL = A.HL, K = A.K, H = A.H, HP = A.HP, F = LOPT_D_VELO, P = A.P;
+  const int W64 = ((K > P ? K : P) + 63) & ~63;
   float* sh_h = sh;
   float* sh_a = sh + HL;
+  float* part = sh_a + K;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
   float* hstate = T.st + 4 * (size_t)T.padN + 3 * (size_t)T.padm + 3 * (size_t)T.padn;
-  for (int i = threadIdx.x; i < HL; i += kBlock) {
+  for (int i = threadIdx.x; i < HL; i += blockDim.x) {
     const float v = h_new[(size_t)blockIdx.x * HL + i];
     sh_h[i] = v;
     hstate[i] = v;
   }
-  __syncthreads();
-  for (int q = threadIdx.x; q < K; q += kBlock) {
-    float a = W.ba[q];
-    for (int k = 0; k < HL; ++k) a += sh_h[k] * W.Wa[(size_t)k * K + q];
-    sh_a[q] = a;
-  }
-  // zero the padded layout first (padding must be zero)
+  // zero the padded layout (padding must be zero); disjoint from everything read below
   float* prep = ws + T.oPrep;
   const int prep_n = (F + 1) * HP + HP * HP + HP + 2 * HP + 2;
-  for (int i = threadIdx.x; i < prep_n; i += kBlock) prep[i] = 0.f;
+  for (int i = threadIdx.x; i < prep_n; i += blockDim.x) prep[i] = 0.f;
+  __syncthreads();
+  // alpha = h W_a: wavefront w reduces rows w, w+nw, ...; a lane owns four output columns 64 apart
+  for (int q0 = 0; q0 < K; q0 += 256) matvec4(sh_h, HL, W.Wa, K, q0, wave, nw, lane, part, W64);
+  __syncthreads();
+  for (int q = threadIdx.x; q < K; q += blockDim.x)
+  {
+    float a = W.ba[q];
+    for (int w = 0; w < nw; ++w) a += part[w * W64 + q];
+    sh_a[q] = a;
+  }
+  __syncthreads();
+  // theta = alpha B, same scheme
+  for (int i0 = 0; i0 < P; i0 += 256) matvec4(sh_a, K, W.B, P, i0, wave, nw, lane, part, W64);
   __syncthreads();
   const float* scale = ws + T.oScale;
-  const int P = A.P;
-  for (int i = threadIdx.x; i < P; i += kBlock) {
+  for (int i = threadIdx.x; i < P; i += blockDim.x) {
     float th = 0.f;
-    for (int q = 0; q < K; ++q) th += sh_a[q] * W.B[(size_t)q * P + i];
+    for (int w = 0; w < nw; ++w) th += part[w * W64 + i];
     // scatter from the compact layout (W1[F,H] b1[H] W2[H,H] b2[H] W3[H,2] b3[2]) to the padded one
     int o = i, dst;
     if (o < F * H) { const int f = o / H, u = o - f * H; dst = f * HP + u; th *= scale[f]; }
@@ -502,8 +562,11 @@ __global__ void __launch_bounds__(kBlock) k_velo_head(const TensorDev* __restric
 
 void launch_velo_head(const Launch& L, const StepArgs& A, const WeightsDev& W, const float* h_new, hipStream_t s) {
   if (L.n_tensors == 0) return;
-  size_t shmem = (size_t)(A.HL + A.K) * sizeof(float);
-  hipLaunchKernelGGL(k_velo_head, dim3(L.n_tensors), dim3(kBlock), shmem, s, L.tensors, L.ws, A, W, h_new);
+  const int W64 = ((A.K > A.P ? A.K : A.P) + 63) & ~63;
+  int nw = 16;  // wavefronts per workgroup = ways the reductions are split; bounded by 48 KB of partials
+  while (nw > 1 && (size_t)nw * W64 * sizeof(float) > 48 * 1024) nw >>= 1;
+  size_t shmem = (size_t)(A.HL + A.K + nw * W64) * sizeof(float);
+  hipLaunchKernelGGL(k_velo_head, dim3(L.n_tensors), dim3(64 * nw), shmem, s, L.tensors, L.ws, A, W, h_new);
 }
 
 }  // namespace lopt
