@@ -32,6 +32,16 @@ APPLY_FLOP_SMALL_FC = 2 * (28 * 32 + 32 * 32 + 32 * 2)
 APPLY_BYTES = 28
 ACCUM_BYTES = 40
 
+# HBM bytes per launch of the dominant kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and
+# scaled by the factors a plain 256 MiB copy gives (2.0 / 1.0): see profiles/hbm_traffic_vit_b16.md.
+# Keyed by (config, pass); other configurations report null.
+MEASURED_TRAFFIC_BYTES = {
+    (2, "apply"): (1_027_000 * 2.0 + 338_200) * 1024,
+    (2, "accum_stats"): (1_024_000 * 2.0 + 1_353_000) * 1024,
+    (3, "apply"): (1_028_000 * 2.0 + 338_200) * 1024,
+    (3, "accum_stats"): (1_024_000 * 2.0 + 1_353_000) * 1024,
+}
+
 
 def cpu_baseline(config_id: int, optimizer: str):
     """The CPU oracle, as it stands, on a bounded sample of the same workload."""
@@ -72,6 +82,8 @@ def main():
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--optimizer", default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device-to-device copy kernel (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build targets one GPU; --gpus must be 1 (no collectives, no sharding here)",
@@ -106,6 +118,13 @@ def main():
                      step=step)
             step += 1
 
+    if args.calibrate_copy:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)   # 256 MiB read + 256 MiB written
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     run(args.warmup)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -144,7 +163,8 @@ def main():
         achieved = per * n_el / dur_s / 1e9
         kernel = dominant
     roofline = {"bound": bound, "kernel": kernel, "achieved": achieved, "peak": peak, "unit": unit,
-                "frac": achieved / peak, "traffic": None,
+                "frac": achieved / peak, "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, dominant)),
+                "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE x2 + WRITE_SIZE, see profiles/)",
                 "avg_launch_ms": pass_ms[dominant], "pass_ms": pass_ms,
                 "ms_per_step_with_events": dt_prof / args.steps * 1e3}
     # every HBM-bound pass against the 8 TB/s roof (algorithmic bytes per element: 4 / 40 / 28)
