@@ -58,3 +58,47 @@ def test_tall_and_wide_tensors():
     cfg = Hn.make_cfg("small_fc_lopt")
     w = W.small_fc_weights(1, 32)
     Hn.run_free(Hn.Case(104, _specs([(9000, 256), (5504,), (4100, 8)]), "student_t3"), cfg, w, 3)
+
+
+@pytest.mark.parametrize("variant", ["valu", "mfma_f32", "mfma_f16x3"])
+def test_every_apply_kernel_variant_matches_the_oracle(variant, monkeypatch):
+    # LOPT_APPLY (read when the context is created) selects the apply kernel for hidden width 32:
+    # vector ALU, fp32 MFMA, or split-fp16 MFMA (the default). All three must meet the same bar.
+    monkeypatch.setenv("LOPT_APPLY", variant)
+    cfg = Hn.make_cfg("small_fc_lopt")
+    w = W.small_fc_weights(2, 32)
+    shapes = [(256, 256), (256,), (64, 256), (300, 257), (33, 1000), (7,)]
+    worst = Hn.run_free(Hn.Case(105, _specs(shapes), "student_t3"), cfg, w, 6, lr_fn=lambda t: 0.8, wd=0.01)
+    assert worst["param"] <= Hn.TOL_PARAM
+
+
+def test_velo_vector_alu_variant_matches_the_oracle(monkeypatch):
+    monkeypatch.setenv("LOPT_APPLY", "valu")
+    cfg = Hn.make_cfg("velo")
+    Hn.run_free(Hn.Case(106, W.config1_shapes(), "gauss_logscale"), cfg, W.velo_weights(1), 4, wd=0.01)
+
+
+@pytest.mark.parametrize("kind", ["small_fc_lopt", "velo"])
+def test_degenerate_gradients(kind):
+    # an all-zero gradient, a constant gradient (rank one, zero variance), one huge outlier, tiny magnitudes
+    cfg = Hn.make_cfg(kind)
+    w = Hn.random_weights(cfg, 4)
+    shapes = [(64, 256), (64, 256), (64, 256), (64, 256), (300,)]
+
+    class Degenerate(Hn.Case):
+        def grad(self, i, step):
+            g = super().grad(i, step)
+            if i == 0:
+                g[:] = 0.0
+            elif i == 1:
+                g[:] = 3e-4
+            elif i == 2:
+                g[5, 7] = 50.0
+            elif i == 3:
+                g *= np.float32(1e-12)
+            else:
+                g[:] = 0.0
+            return g
+
+    worst = Hn.run_free(Degenerate(107, _specs(shapes)), cfg, w, 3)
+    assert np.isfinite(worst["param"])
