@@ -29,3 +29,10 @@ def load_paper_constants():
 @pytest.fixture(scope="session")
 def paper_constants():
     return load_paper_constants()
+
+
+# A planted mistake for tests/test_oracle_mutations.py (applied to the oracle on the CPU only).
+if os.environ.get("ORACLE_MUTATION"):
+    from oracle import lopt_oracle as _O
+    from tests.oracle_mutations import MUTATIONS as _M
+    _M[os.environ["ORACLE_MUTATION"]](_O)
