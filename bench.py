@@ -83,6 +83,8 @@ def main():
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--optimizer", default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--n-tiny", type=int, default=None,
+                    help="config 5 only: number of extra tiny 1-D tensors (default 2000)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device-to-device copy kernel (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -96,6 +98,8 @@ def main():
     import paper_2506_10315_amd as P
 
     wl = W.get_workload(args.config, args.optimizer)
+    if args.config == 5 and args.n_tiny is not None:
+        wl.tensors = W.llama_1p3b_shapes(args.n_tiny)
     optimizer = wl.optimizer
     dev = "cuda:0"
     kind = P.LOPT_SMALL_FC if optimizer == "small_fc_lopt" else P.LOPT_VELO

@@ -6,7 +6,7 @@ import os
 from typing import List, Optional, Sequence
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "liblopt.so")
+_LIB_PATH = os.environ.get("LOPT_LIB_PATH") or os.path.join(_HERE, "liblopt.so")   # override: A/B builds
 
 LOPT_SMALL_FC = 0
 LOPT_VELO = 1

@@ -37,21 +37,23 @@ def _run(cmd):
     return out
 
 
-def build(verbose: bool = False, jobs: int = 6) -> str:
+def build(verbose: bool = False, jobs: int = 6, out: str = OUT, extra_defs=(), obj_dir: str = OBJ) -> str:
+    """Compile every translation unit (in parallel) and link liblopt.so. `out`, `extra_defs` and `obj_dir`
+    exist for A/B builds of experimental variants; the product build uses the defaults."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    os.makedirs(OBJ, exist_ok=True)
+    os.makedirs(obj_dir, exist_ok=True)
     objs = []
     cmds = []
     for src, tag, defs in UNITS:
-        o = os.path.join(OBJ, tag + ".o")
+        o = os.path.join(obj_dir, tag + ".o")
         objs.append(o)
-        cmds.append([hipcc, *FLAGS, *defs, "-c", os.path.join(CSRC, src), "-o", o])
+        cmds.append([hipcc, *FLAGS, *defs, *extra_defs, "-c", os.path.join(CSRC, src), "-o", o])
     with ThreadPoolExecutor(max_workers=jobs) as ex:
-        for out in ex.map(_run, cmds):
-            if verbose and out.strip():
-                print(out)
-    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", OUT])
-    return OUT
+        for log in ex.map(_run, cmds):
+            if verbose and log.strip():
+                print(log)
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", out])
+    return out
 
 
 if __name__ == "__main__":

@@ -68,12 +68,12 @@ struct ApplyLds {
 template <bool VEC>
 __device__ __forceinline__ void load_row(const TensorDev& T, size_t ro, int col, int n, float4 (&d)[6]) {
   const size_t pN = T.padN;
-  d[0] = load4<VEC>(T.g + ro, col, n);
-  d[1] = load4<VEC>(T.p + ro, col, n);
-  d[2] = load4<VEC>(T.st + ro, col, n);
-  d[3] = load4<VEC>(T.st + pN + ro, col, n);
-  d[4] = load4<VEC>(T.st + 2 * pN + ro, col, n);
-  d[5] = load4<VEC>(T.st + 3 * pN + ro, col, n);
+  d[0] = load4s<VEC>(T.g + ro, col, n);
+  d[1] = load4s<VEC>(T.p + ro, col, n);
+  d[2] = load4s<VEC>(T.st + ro, col, n);
+  d[3] = load4s<VEC>(T.st + pN + ro, col, n);
+  d[4] = load4s<VEC>(T.st + 2 * pN + ro, col, n);
+  d[5] = load4s<VEC>(T.st + 3 * pN + ro, col, n);
 }
 
 // Per-tile set-up shared by the matrix-core apply kernels: the column vectors of the hoisted

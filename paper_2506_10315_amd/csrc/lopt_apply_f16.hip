@@ -209,7 +209,7 @@ __device__ __forceinline__ void apply_f16_tile(const TensorDev& T, const TileDev
       pn[e] = p - lr * (delta + wd * p);
       __builtin_amdgcn_sched_barrier(0);   // keep the four rounds apart: bounds register pressure
     }
-    store4<VEC>(T.p + ro, col, n, make_float4(pn[0], pn[1], pn[2], pn[3]));
+    store4s<VEC>(T.p + ro, col, n, make_float4(pn[0], pn[1], pn[2], pn[3]));
 #pragma unroll
     for (int i = 0; i < 6; ++i) cur[i] = nxt[i];
   }

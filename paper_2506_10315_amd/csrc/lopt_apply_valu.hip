@@ -42,12 +42,12 @@ __device__ __forceinline__ void apply_tile(const TensorDev& T, const TileDev& ti
   const float lr = A.lr, wd = A.wd;
   for (int r = r0 + wave; r < r1; r += 4) {
     const size_t ro = (size_t)r * n;
-    const float4 g4 = load4<VEC>(T.g + ro, col, n);
-    const float4 p4 = load4<VEC>(T.p + ro, col, n);
-    const float4 m1 = load4<VEC>(M1 + ro, col, n);
-    const float4 m2 = load4<VEC>(M2 + ro, col, n);
-    const float4 m3 = load4<VEC>(M3 + ro, col, n);
-    const float4 v4 = load4<VEC>(Vp + ro, col, n);
+    const float4 g4 = load4s<VEC>(T.g + ro, col, n);
+    const float4 p4 = load4s<VEC>(T.p + ro, col, n);
+    const float4 m1 = load4s<VEC>(M1 + ro, col, n);
+    const float4 m2 = load4s<VEC>(M2 + ro, col, n);
+    const float4 m3 = load4s<VEC>(M3 + ro, col, n);
+    const float4 v4 = load4s<VEC>(Vp + ro, col, n);
     float rr[3], rv[3];
 #pragma unroll
     for (int k = 0; k < 3; ++k) {
@@ -128,7 +128,7 @@ __device__ __forceinline__ void apply_tile(const TensorDev& T, const TileDev& ti
         pn[e0 + e] = p - lr * (delta + wd * p);
       }
     }
-    store4<VEC>(T.p + ro, col, n, make_float4(pn[0], pn[1], pn[2], pn[3]));
+    store4s<VEC>(T.p + ro, col, n, make_float4(pn[0], pn[1], pn[2], pn[3]));
   }
 }
 

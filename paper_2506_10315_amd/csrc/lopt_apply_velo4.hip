@@ -10,6 +10,10 @@
 #include "lopt_internal.h"
 #include "lopt_device.h"
 
+#ifndef LOPT_V4_STORE
+#define LOPT_V4_STORE store4s
+#endif
+
 namespace lopt {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -86,12 +90,12 @@ __device__ __forceinline__ void apply_velo4_tile(const TensorDev& T, const TileD
 
   for (int r = r0 + wave; r < r1; r += 4) {
     const size_t ro = (size_t)r * n;
-    const float4 g4 = load4<VEC>(T.g + ro, col, n);
-    const float4 p4 = load4<VEC>(T.p + ro, col, n);
-    const float4 m1 = load4<VEC>(M1 + ro, col, n);
-    const float4 m2 = load4<VEC>(M2 + ro, col, n);
-    const float4 m3 = load4<VEC>(M3 + ro, col, n);
-    const float4 v4 = load4<VEC>(Vp + ro, col, n);
+    const float4 g4 = load4s<VEC>(T.g + ro, col, n);
+    const float4 p4 = load4s<VEC>(T.p + ro, col, n);
+    const float4 m1 = load4s<VEC>(M1 + ro, col, n);
+    const float4 m2 = load4s<VEC>(M2 + ro, col, n);
+    const float4 m3 = load4s<VEC>(M3 + ro, col, n);
+    const float4 v4 = load4s<VEC>(Vp + ro, col, n);
     float rr[3], rv[3];
 #pragma unroll
     for (int k = 0; k < 3; ++k) {
@@ -154,7 +158,7 @@ __device__ __forceinline__ void apply_velo4_tile(const TensorDev& T, const TileD
       const float p = get(p4, e);
       pn[e] = p - lr * (delta + wd * p);
     }
-    store4<VEC>(T.p + ro, col, n, make_float4(pn[0], pn[1], pn[2], pn[3]));
+    LOPT_V4_STORE<VEC>(T.p + ro, col, n, make_float4(pn[0], pn[1], pn[2], pn[3]));
   }
 }
 
