@@ -83,6 +83,8 @@ def main():
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--optimizer", default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--micro", default=None,
+                    help="time a micro-workload instead of a numbered config: layer1000 or mlp_w<W>_d<D>")
     ap.add_argument("--n-tiny", type=int, default=None,
                     help="config 5 only: number of extra tiny 1-D tensors (default 2000)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -98,6 +100,9 @@ def main():
     import paper_2506_10315_amd as P
 
     wl = W.get_workload(args.config, args.optimizer)
+    if args.micro:
+        wl = W.micro_workload(args.micro, args.optimizer or "small_fc_lopt")
+        args.config = wl.config_id
     if args.config == 5 and args.n_tiny is not None:
         wl.tensors = W.llama_1p3b_shapes(args.n_tiny)
     optimizer = wl.optimizer
@@ -180,13 +185,13 @@ def main():
         "metric": "optimizer-step throughput", "value": n_el / (dt / args.steps) / 1e9, "unit": "Gparams/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"config {args.config}: {optimizer} on {wl.name} shapes "
+        "config": {"workload": f"{'micro' if args.micro else 'config ' + str(args.config)}: {optimizer} on {wl.name} shapes "
                                f"({n} tensors, {n_el} fp32 elements), all tensors in one lopt_step",
                    "optimizer": optimizer, "hidden": int(cfg.hidden)},
         "finite": finite,
         "roofline": roofline,
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.micro:
         out["cpu_baseline"] = cpu_baseline(args.config, optimizer)
     opt.close()
     print(json.dumps(out))

@@ -132,6 +132,29 @@ def llama_1p3b_shapes(n_tiny: int = 2000) -> List[TensorSpec]:
     return t
 
 
+def mlp_shapes(width: int, depth: int, in_dim: int = 1024, out_dim: int = 10) -> List[TensorSpec]:
+    """Optimizee MLP with `depth` hidden layers of `width` units (the paper's controlled width/depth
+    sweeps; it does not state input/output sizes, 1024 and 10 are this project's choice)."""
+    dims = [in_dim] + [width] * depth + [out_dim]
+    t = []
+    for i in range(len(dims) - 1):
+        t += [TensorSpec(f"fc{i}.weight", (dims[i + 1], dims[i])), TensorSpec(f"fc{i}.bias", (dims[i + 1],))]
+    return t
+
+
+def micro_workload(name: str, optimizer: str = "small_fc_lopt") -> Workload:
+    """The paper's micro-workloads as shapes: 'layer1000' = one 1000x1000 weight without bias (its profiler
+    figure); 'mlp_w<W>_d<D>' = MLP of width W and depth D (its scaling figure)."""
+    if name == "layer1000":
+        tensors = [TensorSpec("fc.weight", (1000, 1000))]
+    elif name.startswith("mlp_w"):
+        w, d = name[5:].split("_d")
+        tensors = mlp_shapes(int(w), int(d))
+    else:
+        raise ValueError(name)
+    return Workload(100, name, optimizer, tensors, 40, "gauss_logscale")
+
+
 def get_workload(config_id: int, optimizer: str | None = None) -> Workload:
     """The five benchmark configurations (config 4 exists for both optimizers)."""
     if config_id == 1:
