@@ -136,6 +136,13 @@ void build_plan(const lopt_ctx* ctx, size_t n, const lopt_tensor_desc* d, Plan* 
     pl->oLstmU = take((uint64_t)n * kLstmInPad);
     pl->oHNew = take((uint64_t)n * ctx->cfg.lstm_hidden);
   }
+  // Small parameter sets: with the standard 64-row tiles there may be fewer tiles than the chip has workgroup
+  // slots (256 CUs x 2..8), so the tile height is halved until the list yields about 2048 tiles or reaches 8 rows.
+  uint64_t std_tiles = 0;
+  for (size_t i = 0; i < n; ++i)
+    std_tiles += (uint64_t)((d[i].rows + kRowUnit - 1) / kRowUnit) * (uint64_t)((d[i].cols + kTileCols - 1) / kTileCols);
+  int shrink = 1;
+  while (shrink < 8 && std_tiles * shrink < 2048) shrink *= 2;
   for (size_t i = 0; i < n; ++i) {
     TensorDev& T = pl->tensors[i];
     const int m = (int)d[i].rows, nn = (int)d[i].cols;
@@ -147,7 +154,10 @@ void build_plan(const lopt_ctx* ctx, size_t n, const lopt_tensor_desc* d, Plan* 
     T.vec = (nn % 4 == 0) ? 1 : 0;
     const int units = (m + kRowUnit - 1) / kRowUnit;
     const int q = (units + kMaxRowTiles - 1) / kMaxRowTiles;
-    T.TR = kRowUnit * (q < 1 ? 1 : q);
+    T.TR = kRowUnit * (q < 1 ? 1 : q) / shrink;   // a multiple of 8: every wavefront of a tile owns whole rows
+    // ... but never more than kMaxRowTiles row tiles per tensor (the second-stage reductions loop over them)
+    const int min_tr = ((m + kMaxRowTiles - 1) / kMaxRowTiles + 7) & ~7;
+    if (T.TR < min_tr) T.TR = min_tr;
     T.nrt = (m + T.TR - 1) / T.TR;
     T.nct = (nn + kTileCols - 1) / kTileCols;
     T.tile0 = (int)pl->tiles.size();

@@ -132,7 +132,8 @@ __global__ void __launch_bounds__(kBlock) k_rc_update(const TensorDev* __restric
     if (idx < T.m) {
       const float* part = ws + T.oRowPart + idx;
       double acc = 0.0;
-      for (int j = 0; j < T.nct; ++j) acc += (double)part[(size_t)j * T.m];
+#pragma unroll 8
+      for (int j = 0; j < T.nct; ++j) acc += (double)part[(size_t)j * T.m];   // loads issue ahead, adds stay in order
       const float R = (float)(acc / (double)T.n);
 #pragma unroll
       for (int k = 0; k < 3; ++k) {
@@ -151,6 +152,7 @@ __global__ void __launch_bounds__(kBlock) k_rc_update(const TensorDev* __restric
     if (idx < T.n) {
       const float* part = ws + T.oColPart + idx;
       double acc = 0.0;
+#pragma unroll 8
       for (int i = 0; i < T.nrt; ++i) acc += (double)part[(size_t)i * T.n];
       const float C = (float)(acc / (double)T.m);
 #pragma unroll
@@ -297,6 +299,7 @@ __global__ void __launch_bounds__(kBlock) k_finalize(const TensorDev* __restrict
   double a = 0.0;
   if (q < kNStat) {
     const float* sp = ws + T.oStatPart + q;
+#pragma unroll 8
     for (int i = seg; i < ntiles; i += 8) a += (double)sp[(size_t)i * kStatStride];
   }
   part[seg][q] = a;
@@ -311,9 +314,11 @@ __global__ void __launch_bounds__(kBlock) k_finalize(const TensorDev* __restrict
   a = 0.0;
   if (q < 9) {
     const float* rp = ws + T.oRcPart + q;
+#pragma unroll 4
     for (int i = seg; i < T.nrblk; i += 8) a += (double)rp[(size_t)i * kRcStride];
   } else if (q >= 16 && q < 25) {
     const float* cp = ws + T.oRcPart + (size_t)T.nrblk * kRcStride + (q - 16);
+#pragma unroll 4
     for (int i = seg; i < T.ncblk; i += 8) a += (double)cp[(size_t)i * kRcStride];
   }
   part[seg][q] = a;
