@@ -316,7 +316,7 @@ lopt_status lopt_create(const lopt_config* cfg, const float* weights_host, size_
   if (!ctx) return fail(nullptr, LOPT_ENOMEM, "out of host memory");
   ctx->cfg = *cfg;
   if (const char* e = getenv("LOPT_APPLY")) {
-    ctx->apply_variant = !strcmp(e, "valu") ? 1 : !strcmp(e, "mfma_f32") ? 2 : !strcmp(e, "mfma_f16x3") ? 3 : 0;
+    ctx->apply_variant = !strcmp(e, "valu") ? 1 : !strcmp(e, "mfma_f32") ? 2 : !strcmp(e, "mfma_f16x3") ? 3 : !strcmp(e, "mfma_f16s") ? 4 : 0;
   }
   const int H = (int)cfg->hidden;
   ctx->HP = padded_hidden(H);
@@ -512,7 +512,8 @@ lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, fl
     MARK(6);
   }
   const bool mfma_ok = apply_mfma_available(A);
-  if (mfma_ok && (ctx->apply_variant == 0 || ctx->apply_variant == 3)) launch_apply_f16x3(L, A, ctx->W, stream);
+  if (mfma_ok && ctx->apply_variant == 4) launch_apply_f16s(L, A, ctx->W, stream);
+  else if (mfma_ok && (ctx->apply_variant == 0 || ctx->apply_variant == 3)) launch_apply_f16x3(L, A, ctx->W, stream);
   else if (mfma_ok && ctx->apply_variant == 2) launch_apply_mfma(L, A, ctx->W, stream);
   else if (ctx->cfg.kind == LOPT_SMALL_FC) launch_apply_small_fc(L, A, ctx->W, stream);
   else if (ctx->apply_variant != 1 && apply_velo4_available(A)) launch_apply_velo4(L, A, stream);

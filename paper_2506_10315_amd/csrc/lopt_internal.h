@@ -94,5 +94,6 @@ void launch_apply_mfma(const Launch&, const StepArgs&, const WeightsDev&, hipStr
 bool apply_velo4_available(const StepArgs&);
 void launch_apply_velo4(const Launch&, const StepArgs&, hipStream_t);
 void launch_apply_f16x3(const Launch&, const StepArgs&, const WeightsDev&, hipStream_t);
+void launch_apply_f16s(const Launch&, const StepArgs&, const WeightsDev&, hipStream_t);
 
 }  // namespace lopt

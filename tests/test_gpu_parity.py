@@ -60,7 +60,7 @@ def test_tall_and_wide_tensors():
     Hn.run_free(Hn.Case(104, _specs([(9000, 256), (5504,), (4100, 8)]), "student_t3"), cfg, w, 3)
 
 
-@pytest.mark.parametrize("variant", ["valu", "mfma_f32", "mfma_f16x3"])
+@pytest.mark.parametrize("variant", ["valu", "mfma_f32", "mfma_f16x3", "mfma_f16s"])
 def test_every_apply_kernel_variant_matches_the_oracle(variant, monkeypatch):
     # LOPT_APPLY (read when the context is created) selects the apply kernel for hidden width 32:
     # vector ALU, fp32 MFMA, or split-fp16 MFMA (the default). All three must meet the same bar.
