@@ -161,12 +161,14 @@ def main():
     if dominant == "apply" and optimizer == "small_fc_lopt" and variant != "valu":
         # the MLP contraction runs on the matrix cores: fp32 MFMA (variant mfma_f32) or three fp16 MFMA terms
         # per product (default); either way the algorithmic work is the fp32 contraction of the paper's MLP
-        f16 = variant in ("auto", "mfma_f16x3")
+        f16 = variant in ("auto", "mfma_f16x3", "mfma_f16s")
         bound, unit = "mfma", "TFLOP/s"
         peak = MFMA_F16_PEAK_TFLOPS if f16 else MFMA_F32_PEAK_TFLOPS
         achieved = APPLY_FLOP_SMALL_FC * n_el / dur_s / 1e12
-        kernel = "apply (k_apply_f16x3: fp16 hi+lo operands, 3 MFMA terms, fp32 accumulate)" if f16 else \
-                 "apply (k_apply_mfma: fp32 MFMA)"
+        kernel = ("apply (k_apply_f16x3: fp16 hi+lo operands, 3 MFMA terms, fp32 accumulate, row form)"
+                  if variant == "mfma_f16x3" else
+                  "apply (k_apply_f16s: fp16 hi+lo operands, 3 MFMA terms, fp32 accumulate, column strips, "
+                  "software-pipelined)" if f16 else "apply (k_apply_mfma: fp32 MFMA)")
     else:
         bound, unit, peak = "hbm", "GB/s", HBM_PEAK_GBS
         per = APPLY_BYTES if dominant == "apply" else ACCUM_BYTES if dominant == "accum_stats" else 4

@@ -12,12 +12,18 @@
  *  - Every pointer named *_host is host memory; params, grads, state blobs and the
  *    workspace are DEVICE memory owned by the caller (fp32, 16-byte aligned).
  *  - The library owns only the lopt_ctx: a device copy of the optimizer's weights,
- *    a cached device table describing the tensor list, and a pinned staging buffer.
+ *    a cached device table describing the tensor list, a pinned staging buffer and
+ *    (small_fc_lopt) one extra stream with its events.
  *    lopt_step allocates device memory only when the tensor list changes.
- *  - All device work is enqueued on the HIP stream passed in (a hipStream_t cast to
- *    void*, NULL = default stream). No call synchronizes the host with the device
- *    except when a cached table has to be rewritten while its previous upload is
- *    still in flight.
+ *  - All device work is ordered by the HIP stream passed in (a hipStream_t cast to
+ *    void*, NULL = default stream): it starts after everything enqueued on that
+ *    stream before the call and is complete before anything enqueued on it after
+ *    the call. For large small_fc_lopt lists lopt_step cuts the list into groups and
+ *    runs the HBM-bound passes of one group on a library-owned second stream beside
+ *    the compute-bound apply pass of the previous group; that stream forks from and
+ *    joins back into the caller's stream through events inside the same call.
+ *    No call synchronizes the host with the device except when a cached table has to
+ *    be rewritten while its previous upload is still in flight.
  *  - Every call validates its arguments on the host before launching anything and
  *    returns a status; nothing throws or aborts across this boundary. After a
  *    non-OK status, params and state are untouched and lopt_last_error() gives a
@@ -105,7 +111,13 @@ size_t lopt_weights_count(const lopt_config* cfg);
  * before returning and may be freed afterwards. *out is set only on LOPT_OK.
  * Errors: LOPT_EINVAL (null, struct_size, hidden/lstm_hidden/n_bank out of range, decay
  * outside [0,1), negative eps), LOPT_ESTATE (n_weights != lopt_weights_count), LOPT_ENOMEM,
- * LOPT_EHIP. */
+ * LOPT_EHIP.
+ * Tuning knobs read from the environment here (none changes what is computed beyond rounding):
+ *   LOPT_APPLY = valu | mfma_f32 | mfma_f16x3 | mfma_f16s   apply kernel for hidden width 32
+ *                (default mfma_f16s: split-fp16 matrix cores, column strips, software-pipelined)
+ *   LOPT_GROUPS = 1..16   number of tensor groups of the two-stream pipeline (default by list size;
+ *                1 = every pass over the whole list, one after the other, on the caller's stream)
+ *   LOPT_SHADOW_LDS_KB    unused LDS requested by the streaming passes that run beside an apply pass */
 lopt_status lopt_create(const lopt_config* cfg, const float* weights_host, size_t n_weights,
                         lopt_ctx** out);
 
@@ -161,7 +173,8 @@ lopt_status lopt_stats_offsets(const lopt_ctx* ctx, size_t n, const lopt_tensor_
 /* Per-pass timing for benchmarks. lopt_step is a fixed sequence of LOPT_N_PASSES kernel launches
  * (a pass that a configuration does not use records zero time):
  *   0 rowcol_sums  1 rc_update  2 accum_stats  3 finalize  4 velo_lstm  5 velo_head  6 apply
- * With profiling enabled, lopt_step brackets every launch with HIP events on the caller's stream.
+ * With profiling enabled, lopt_step runs every pass over the whole list on the caller's stream (no
+ * tensor groups, no second stream) and brackets every launch with HIP events on that stream.
  * lopt_profile_read waits for the recorded events, adds up the elapsed milliseconds per pass over
  * all steps since the last read (ms_per_pass[LOPT_N_PASSES], may not be null), stores the number of
  * steps in *n_steps (may be null) and clears the record. lopt_pass_name returns a static string,

@@ -16,6 +16,8 @@ namespace {
 
 thread_local std::string g_last_error;
 
+constexpr int kMaxGroups = 16;
+
 inline uint32_t pad4(uint64_t x) { return (uint32_t)((x + 3) & ~(uint64_t)3); }
 inline uint64_t align64(uint64_t x) { return (x + 63) & ~(uint64_t)63; }
 
@@ -51,6 +53,9 @@ struct Plan {
   std::vector<TensorDev> tensors;   // pointers filled per call
   std::vector<TileDev> tiles;
   std::vector<RcItemDev> rcitems;
+  std::vector<ApplyTileDev> atiles;   // tiles of the strip-form apply kernel
+  std::vector<int> atile0;            // first apply tile of every tensor
+  uint64_t total_elems = 0;
   std::vector<size_t> state_bytes;
   uint64_t oLstmU = 0, oHNew = 0;   // VeLO scratch (floats)
   uint64_t ws_floats = 0;
@@ -73,6 +78,7 @@ struct lopt_ctx {
   TensorDev* d_tensors = nullptr;
   TileDev* d_tiles = nullptr;
   RcItemDev* d_rcitems = nullptr;
+  ApplyTileDev* d_atiles = nullptr;
   bool static_uploaded = false;    // tiles + rcitems are on the device
   std::vector<TensorDev> last_tensors;  // what d_tensors currently holds
   bool tensors_uploaded = false;
@@ -80,7 +86,15 @@ struct lopt_ctx {
   size_t h_stage_bytes = 0;
   hipEvent_t stage_ev = nullptr;
   bool stage_pending = false;
-  int apply_variant = 0;           // 0 auto, 1 vector ALU, 2 fp32 MFMA, 3 split-fp16 MFMA (LOPT_APPLY in the environment at create)
+  int apply_variant = 0;           // 0 auto, 1 vector ALU, 2 fp32 MFMA, 3 split-fp16 MFMA row form, 4 strip form (LOPT_APPLY in the environment at create)
+  // Group pipeline (small_fc_lopt, strip-form apply): the tensor list is cut into groups; the HBM-bound passes of
+  // group g+1 run on `aux_stream` while the compute-bound apply pass of group g runs on the caller's stream.
+  int groups_override = 0;         // LOPT_GROUPS in the environment at create (0 = choose by size)
+  unsigned shadow_lds = 72 * 1024; // LDS ballast of the streaming passes that run beside an apply pass: at most one of
+                                   // their workgroups fits on a CU next to the apply pass's two (LOPT_SHADOW_LDS_KB)
+  hipStream_t aux_stream = nullptr;
+  hipEvent_t ev_fork = nullptr;
+  std::vector<hipEvent_t> ev_start, ev_pre;   // per group: "previous group's passes are enqueued" / "this group's passes are done"
   // optional per-pass timing
   bool profiling = false;
   std::vector<hipEvent_t> prof_events;   // (LOPT_N_PASSES + 1) events per recorded step
@@ -126,6 +140,9 @@ void build_plan(const lopt_ctx* ctx, size_t n, const lopt_tensor_desc* d, Plan* 
   pl->tensors.assign(n, TensorDev{});
   pl->tiles.clear();
   pl->rcitems.clear();
+  pl->atiles.clear();
+  pl->atile0.assign(n, 0);
+  pl->total_elems = 0;
   pl->state_bytes.assign(n, 0);
   const bool velo = ctx->cfg.kind == LOPT_VELO;
   const int HP = ctx->HP;
@@ -168,6 +185,13 @@ void build_plan(const lopt_ctx* ctx, size_t n, const lopt_tensor_desc* d, Plan* 
     T.rc0 = (int)pl->rcitems.size();
     for (int b = 0; b < T.nrblk; ++b) pl->rcitems.push_back(RcItemDev{(int)i, 0, b, 0});
     for (int b = 0; b < T.ncblk; ++b) pl->rcitems.push_back(RcItemDev{(int)i, 1, b, 0});
+    // apply tiles: up to kApplyRows x kApplyCols, shorter for small lists like the statistics tiles
+    const int AR = kApplyRows / shrink;
+    pl->atile0[i] = (int)pl->atiles.size();
+    pl->total_elems += N;
+    for (int ar0 = 0; ar0 < m; ar0 += AR)
+      for (int ac0 = 0; ac0 < nn; ac0 += kApplyCols)
+        pl->atiles.push_back(ApplyTileDev{(int)i, ar0, ac0, m - ar0 < AR ? m - ar0 : AR});
     T.oRowPart = take((uint64_t)T.nct * m);
     T.oColPart = take((uint64_t)T.nrt * nn);
     T.oRR = take(3ull * T.padm);
@@ -207,10 +231,10 @@ lopt_status ensure_plan(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* d) {
 // Make sure the device tables exist and hold the current plan and pointers.
 lopt_status upload_tables(lopt_ctx* ctx, hipStream_t stream) {
   Plan& pl = ctx->plan;
-  const size_t nT = pl.tensors.size(), nTi = pl.tiles.size(), nRc = pl.rcitems.size();
+  const size_t nT = pl.tensors.size(), nTi = pl.tiles.size(), nRc = pl.rcitems.size(), nAt = pl.atiles.size();
   const size_t bT = align64(nT * sizeof(TensorDev)), bTi = align64(nTi * sizeof(TileDev)),
-               bRc = align64(nRc * sizeof(RcItemDev));
-  const size_t need = bT + bTi + bRc;
+               bRc = align64(nRc * sizeof(RcItemDev)), bAt = align64(nAt * sizeof(ApplyTileDev));
+  const size_t need = bT + bTi + bRc + bAt;
   if (need == 0) return LOPT_OK;
   if (need > ctx->d_tables_bytes) {
     if (ctx->stage_pending) { HIP_TRY(ctx, hipEventSynchronize(ctx->stage_ev)); ctx->stage_pending = false; }
@@ -232,6 +256,7 @@ lopt_status upload_tables(lopt_ctx* ctx, hipStream_t stream) {
   ctx->d_tensors = (TensorDev*)dbase;
   ctx->d_tiles = (TileDev*)(dbase + bT);
   ctx->d_rcitems = (RcItemDev*)(dbase + bT + bTi);
+  ctx->d_atiles = (ApplyTileDev*)(dbase + bT + bTi + bRc);
   const bool need_tensors = !ctx->tensors_uploaded || ctx->last_tensors.size() != nT ||
                             memcmp(ctx->last_tensors.data(), pl.tensors.data(), nT * sizeof(TensorDev)) != 0;
   const bool need_static = !ctx->static_uploaded;
@@ -249,6 +274,8 @@ lopt_status upload_tables(lopt_ctx* ctx, hipStream_t stream) {
     memcpy(hbase + bT + bTi, pl.rcitems.data(), nRc * sizeof(RcItemDev));
     HIP_TRY(ctx, hipMemcpyAsync(ctx->d_tiles, hbase + bT, nTi * sizeof(TileDev) , hipMemcpyHostToDevice, stream));
     if (nRc) HIP_TRY(ctx, hipMemcpyAsync(ctx->d_rcitems, hbase + bT + bTi, nRc * sizeof(RcItemDev), hipMemcpyHostToDevice, stream));
+    memcpy(hbase + bT + bTi + bRc, pl.atiles.data(), nAt * sizeof(ApplyTileDev));
+    if (nAt) HIP_TRY(ctx, hipMemcpyAsync(ctx->d_atiles, hbase + bT + bTi + bRc, nAt * sizeof(ApplyTileDev), hipMemcpyHostToDevice, stream));
     ctx->static_uploaded = true;
   }
   HIP_TRY(ctx, hipEventRecord(ctx->stage_ev, stream));
@@ -318,6 +345,10 @@ lopt_status lopt_create(const lopt_config* cfg, const float* weights_host, size_
   if (const char* e = getenv("LOPT_APPLY")) {
     ctx->apply_variant = !strcmp(e, "valu") ? 1 : !strcmp(e, "mfma_f32") ? 2 : !strcmp(e, "mfma_f16x3") ? 3 : !strcmp(e, "mfma_f16s") ? 4 : 0;
   }
+  if (const char* e = getenv("LOPT_GROUPS")) {
+    const int g = atoi(e);
+    ctx->groups_override = g < 0 ? 0 : g > kMaxGroups ? kMaxGroups : g;
+  }
   const int H = (int)cfg->hidden;
   ctx->HP = padded_hidden(H);
   ctx->F = cfg->kind == LOPT_SMALL_FC ? LOPT_N_ELEM_FEATS : LOPT_D_VELO;
@@ -337,6 +368,19 @@ lopt_status lopt_create(const lopt_config* cfg, const float* weights_host, size_
   CREATE_TRY(hipMalloc((void**)&ctx->d_weights, n_weights * sizeof(float)));
   CREATE_TRY(hipMemcpy(ctx->d_weights, weights_host, n_weights * sizeof(float), hipMemcpyHostToDevice));
   CREATE_TRY(hipEventCreateWithFlags(&ctx->stage_ev, hipEventDisableTiming));
+  if (cfg->kind == LOPT_SMALL_FC) {
+    CREATE_TRY(hipStreamCreateWithFlags(&ctx->aux_stream, hipStreamNonBlocking));
+    CREATE_TRY(enable_ballast_lds());
+    if (const char* e = getenv("LOPT_SHADOW_LDS_KB")) ctx->shadow_lds = (unsigned)atoi(e) * 1024u;
+    CREATE_TRY(hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming));
+    for (int g = 0; g < kMaxGroups; ++g) {
+      hipEvent_t a = nullptr, b = nullptr;
+      CREATE_TRY(hipEventCreateWithFlags(&a, hipEventDisableTiming));
+      ctx->ev_start.push_back(a);
+      CREATE_TRY(hipEventCreateWithFlags(&b, hipEventDisableTiming));
+      ctx->ev_pre.push_back(b);
+    }
+  }
   if (cfg->kind == LOPT_SMALL_FC) {
     const int HP = ctx->HP;
     // W2 b2 W3 b3 zero-padded to HP, followed by the un-normalized first layer W1[28][HP] (padded)
@@ -382,6 +426,10 @@ void lopt_destroy(lopt_ctx* ctx) {
   if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
   if (ctx->stage_ev) (void)hipEventDestroy(ctx->stage_ev);
   for (hipEvent_t e : ctx->prof_events) (void)hipEventDestroy(e);
+  if (ctx->aux_stream) { (void)hipStreamSynchronize(ctx->aux_stream); (void)hipStreamDestroy(ctx->aux_stream); }
+  if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+  for (hipEvent_t e : ctx->ev_start) (void)hipEventDestroy(e);
+  for (hipEvent_t e : ctx->ev_pre) (void)hipEventDestroy(e);
   delete ctx;
 }
 
@@ -446,7 +494,7 @@ lopt_status lopt_init_state(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* des
   st = upload_tables(ctx, stream);
   if (st != LOPT_OK) return st;
   Launch L{ctx->d_tensors, ctx->d_tiles, ctx->d_rcitems, nullptr, (int)n, (int)ctx->plan.tiles.size(),
-           (int)ctx->plan.rcitems.size()};
+           (int)ctx->plan.rcitems.size(), ctx->d_atiles, (int)ctx->plan.atiles.size(), 0, 0u};
   StepArgs A = make_args(ctx, 0, 0.f, 0.f, (int)n);
   launch_fill_zero(L, A, stream);
   HIP_TRY(ctx, hipGetLastError());
@@ -479,8 +527,81 @@ lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, fl
   if ((st = upload_tables(ctx, stream)) != LOPT_OK) return st;
   // workspace base rounded up to 256 bytes (lopt_state_bytes adds the slack)
   float* ws = (float*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255);
-  Launch L{ctx->d_tensors, ctx->d_tiles, ctx->d_rcitems, ws, (int)n, (int)pl.tiles.size(), (int)pl.rcitems.size()};
+  Launch L{ctx->d_tensors, ctx->d_tiles, ctx->d_rcitems, ws, (int)n, (int)pl.tiles.size(), (int)pl.rcitems.size(),
+           ctx->d_atiles, (int)pl.atiles.size(), 0, 0u};
   StepArgs A = make_args(ctx, step, lr, weight_decay, (int)n);
+  const bool mfma_ok = apply_mfma_available(A);
+  // the strip-form kernel addresses a row pair with 32-bit byte offsets
+  bool strip_ok = mfma_ok && (ctx->apply_variant == 0 || ctx->apply_variant == 4);
+  for (size_t i = 0; strip_ok && i < n; ++i) strip_ok = descs[i].cols < (1 << 28);
+  auto launch_apply = [&](const Launch& La) {
+    if (strip_ok) launch_apply_f16s(La, A, ctx->W, stream);
+    else if (mfma_ok && (ctx->apply_variant == 0 || ctx->apply_variant == 3 || ctx->apply_variant == 4))
+      launch_apply_f16x3(La, A, ctx->W, stream);
+    else if (mfma_ok && ctx->apply_variant == 2) launch_apply_mfma(La, A, ctx->W, stream);
+    else if (ctx->cfg.kind == LOPT_SMALL_FC) launch_apply_small_fc(La, A, ctx->W, stream);
+    else if (ctx->apply_variant != 1 && apply_velo4_available(A)) launch_apply_velo4(La, A, stream);
+    else launch_apply_velo(La, A, ctx->W, stream);
+  };
+  // ---- group pipeline: only where the apply pass is compute-bound (strip form), the list is large enough to
+  // pay for the extra launches, and per-pass timing is off (its events assume one pass after the other)
+  int G = 1;
+  if (strip_ok && ctx->aux_stream && !ctx->profiling) {
+    G = ctx->groups_override ? ctx->groups_override : pl.total_elems >= (256u << 20) ? 8 : pl.total_elems >= (32u << 20) ? 4 : 1;
+    if ((size_t)G > n) G = (int)n;
+  }
+  if (G > 1) {
+    // contiguous tensor ranges of about equal element count
+    int bound[kMaxGroups + 1];
+    {
+      uint64_t cum = 0;
+      int g = 1;
+      bound[0] = 0;
+      for (size_t i = 0; i < n && g < G; ++i) {
+        cum += (uint64_t)descs[i].rows * (uint64_t)descs[i].cols;
+        if (cum * (uint64_t)G >= pl.total_elems * (uint64_t)g && (int)i + 1 > bound[g - 1]) bound[g++] = (int)i + 1;
+      }
+      while (g <= G) bound[g++] = (int)n;
+    }
+    auto sub = [&](int g) {
+      const int t0 = bound[g], t1 = bound[g + 1];
+      Launch S = L;
+      if (t0 >= t1) { S.n_tensors = S.n_tiles = S.n_rcitems = S.n_atiles = 0; return S; }
+      const int tile0 = pl.tensors[t0].tile0, tile1 = t1 < (int)n ? pl.tensors[t1].tile0 : (int)pl.tiles.size();
+      const int rc0 = pl.tensors[t0].rc0, rc1 = t1 < (int)n ? pl.tensors[t1].rc0 : (int)pl.rcitems.size();
+      const int at0 = pl.atile0[t0], at1 = t1 < (int)n ? pl.atile0[t1] : (int)pl.atiles.size();
+      S.tiles = L.tiles + tile0; S.n_tiles = tile1 - tile0;
+      S.rcitems = L.rcitems + rc0; S.n_rcitems = rc1 - rc0;
+      S.atiles = L.atiles + at0; S.n_atiles = at1 - at0;
+      S.tensor0 = t0; S.n_tensors = t1 - t0;
+      return S;
+    };
+    auto passes_before_apply = [&](const Launch& S, hipStream_t s) {
+      launch_rowcol_sums(S, A, s);
+      launch_rc_update(S, A, s);
+      launch_accum_stats(S, A, s);
+      launch_finalize(S, A, ctx->W, ws + pl.oLstmU, s);
+    };
+    hipStream_t aux = ctx->aux_stream;
+    HIP_TRY(ctx, hipEventRecord(ctx->ev_fork, stream));       // aux joins the caller's stream here ...
+    HIP_TRY(ctx, hipStreamWaitEvent(aux, ctx->ev_fork, 0));
+    passes_before_apply(sub(0), stream);
+    for (int g = 0; g < G; ++g) {
+      if (g + 1 < G) {
+        // the next group's HBM-bound passes start when this group's are done, i.e. together with its apply pass
+        HIP_TRY(ctx, hipEventRecord(ctx->ev_start[g + 1], stream));
+        HIP_TRY(ctx, hipStreamWaitEvent(aux, ctx->ev_start[g + 1], 0));
+        Launch Sn = sub(g + 1);
+        Sn.ballast_lds = ctx->shadow_lds;
+        passes_before_apply(Sn, aux);
+        HIP_TRY(ctx, hipEventRecord(ctx->ev_pre[g + 1], aux));
+      }
+      launch_apply(sub(g));
+      if (g + 1 < G) HIP_TRY(ctx, hipStreamWaitEvent(stream, ctx->ev_pre[g + 1], 0));   // ... and is joined back here
+    }
+    HIP_TRY(ctx, hipGetLastError());
+    return LOPT_OK;
+  }
   hipEvent_t* ev = nullptr;
   if (ctx->profiling) {
     const size_t need = (ctx->prof_steps + 1) * (LOPT_N_PASSES + 1);
@@ -511,13 +632,7 @@ lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, fl
     MARK(5);
     MARK(6);
   }
-  const bool mfma_ok = apply_mfma_available(A);
-  if (mfma_ok && ctx->apply_variant == 4) launch_apply_f16s(L, A, ctx->W, stream);
-  else if (mfma_ok && (ctx->apply_variant == 0 || ctx->apply_variant == 3)) launch_apply_f16x3(L, A, ctx->W, stream);
-  else if (mfma_ok && ctx->apply_variant == 2) launch_apply_mfma(L, A, ctx->W, stream);
-  else if (ctx->cfg.kind == LOPT_SMALL_FC) launch_apply_small_fc(L, A, ctx->W, stream);
-  else if (ctx->apply_variant != 1 && apply_velo4_available(A)) launch_apply_velo4(L, A, stream);
-  else launch_apply_velo(L, A, ctx->W, stream);
+  launch_apply(L);
   MARK(7);
 #undef MARK
   HIP_TRY(ctx, hipGetLastError());

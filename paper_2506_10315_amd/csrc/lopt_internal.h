@@ -20,6 +20,11 @@ constexpr int kNStat = 17;        // per-element statistics accumulated per tile
 constexpr int kStatsPerTensor = 32;
 constexpr int kLstmInPad = 48;    // LOPT_VELO_LSTM_IN rounded up
 constexpr int kLstmTensorsPerBlock = 8;
+#ifndef LOPT_APPLY_ROWS
+#define LOPT_APPLY_ROWS 64
+#endif
+constexpr int kApplyRows = LOPT_APPLY_ROWS;   // tile of the strip-form apply kernel: up to this many rows x 128 columns
+constexpr int kApplyCols = 128;
 
 // Per-tensor record in device memory. Offsets o* are in floats from the workspace base.
 struct TensorDev {
@@ -45,6 +50,7 @@ struct TensorDev {
 
 struct TileDev { int tensor, ti, tj, pad; };
 struct RcItemDev { int tensor, is_col, blk, pad; };
+struct ApplyTileDev { int tensor, r0, c0, rows; };   // rows <= kApplyRows
 
 // Scalars of one step, passed by value to the kernels.
 struct StepArgs {
@@ -75,9 +81,14 @@ struct Launch {
   const RcItemDev* rcitems;
   float* ws;
   int n_tensors, n_tiles, n_rcitems;
+  const ApplyTileDev* atiles;
+  int n_atiles;
+  int tensor0;   // first tensor of the sub-list this launch covers (the per-tensor kernels index from it)
+  unsigned ballast_lds;   // bytes of unused dynamic LDS requested by the streaming passes (bounds their workgroups per CU)
 };
 
 // kernels (lopt_kernels.hip / lopt_apply_mfma.hip)
+hipError_t enable_ballast_lds();
 void launch_fill_zero(const Launch&, const StepArgs&, hipStream_t);
 void launch_rowcol_sums(const Launch&, const StepArgs&, hipStream_t);
 void launch_rc_update(const Launch&, const StepArgs&, hipStream_t);

@@ -96,7 +96,7 @@ __global__ void __launch_bounds__(kBlock) k_rowcol_sums(const TensorDev* __restr
 
 void launch_rowcol_sums(const Launch& L, const StepArgs&, hipStream_t s) {
   if (L.n_tiles == 0) return;
-  hipLaunchKernelGGL(k_rowcol_sums, dim3(L.n_tiles), dim3(kBlock), 0, s, L.tensors, L.tiles, L.ws);
+  hipLaunchKernelGGL(k_rowcol_sums, dim3(L.n_tiles), dim3(kBlock), L.ballast_lds, s, L.tensors, L.tiles, L.ws);
 }
 
 // ----------------------------------------------------------------------------- rc_update
@@ -273,9 +273,16 @@ __global__ void __launch_bounds__(kBlock) k_accum_stats(const TensorDev* __restr
   block_sum<kNStat>(acc, red, ws + T.oStatPart + (size_t)lt * kStatStride);
 }
 
+// Called once per context: lets the two streaming kernels take up to the whole LDS as launch-time ballast.
+hipError_t enable_ballast_lds() {
+  hipError_t e = hipFuncSetAttribute((const void*)k_rowcol_sums, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute((const void*)k_accum_stats, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+}
+
 void launch_accum_stats(const Launch& L, const StepArgs& A, hipStream_t s) {
   if (L.n_tiles == 0) return;
-  hipLaunchKernelGGL(k_accum_stats, dim3(L.n_tiles), dim3(kBlock), 0, s, L.tensors, L.tiles, L.ws, A);
+  hipLaunchKernelGGL(k_accum_stats, dim3(L.n_tiles), dim3(kBlock), L.ballast_lds, s, L.tensors, L.tiles, L.ws, A);
 }
 
 // ----------------------------------------------------------------------------- finalize
@@ -283,11 +290,12 @@ void launch_accum_stats(const Launch& L, const StepArgs& A, hipStream_t s) {
 // One workgroup per tensor. Reduces every partial in a fixed order (double accumulation),
 // then writes s_f, the per-feature scale factors and the prepared first layer.
 __global__ void __launch_bounds__(kBlock) k_finalize(const TensorDev* __restrict__ tensors, float* __restrict__ ws,
-                                                     StepArgs A, WeightsDev W, float* __restrict__ lstm_u) {
+                                                     StepArgs A, WeightsDev W, float* __restrict__ lstm_u, int tensor0) {
   __shared__ double part[8][32];
   __shared__ double tot[48];
   __shared__ float s_stats[32], s_scale[32], s_tfeat[LOPT_N_TIME];
-  const TensorDev& T = tensors[blockIdx.x];
+  const int ti = tensor0 + (int)blockIdx.x;
+  const TensorDev& T = tensors[ti];
   if (threadIdx.x >= 64 && threadIdx.x < 64 + LOPT_N_TIME) {
     // time features tanh(t/x) (feature table of small_fc_lopt, row "Time Features")
     const double xs[LOPT_N_TIME] = {1, 3, 10, 30, 100, 300, 1000, 3000, 1e4, 3e4, 1e5};
@@ -373,7 +381,7 @@ __global__ void __launch_bounds__(kBlock) k_finalize(const TensorDev* __restrict
     }
   } else {
     // LSTM input: 0.05*ln(s_f + 1e-30), time features, one-hot of min(ndim, 4)
-    float* u = lstm_u + (size_t)blockIdx.x * kLstmInPad;
+    float* u = lstm_u + (size_t)ti * kLstmInPad;
     const int t = threadIdx.x;
     if (t < LOPT_D_VELO) u[t] = 0.05f * logf(s_stats[t] + 1e-30f);
     else if (t < LOPT_D_VELO + LOPT_N_TIME) u[t] = s_tfeat[t - LOPT_D_VELO];
@@ -386,7 +394,7 @@ __global__ void __launch_bounds__(kBlock) k_finalize(const TensorDev* __restrict
 
 void launch_finalize(const Launch& L, const StepArgs& A, const WeightsDev& W, float* lstm_u, hipStream_t s) {
   if (L.n_tensors == 0) return;
-  hipLaunchKernelGGL(k_finalize, dim3(L.n_tensors), dim3(kBlock), 0, s, L.tensors, L.ws, A, W, lstm_u);
+  hipLaunchKernelGGL(k_finalize, dim3(L.n_tensors), dim3(kBlock), 0, s, L.tensors, L.ws, A, W, lstm_u, L.tensor0);
 }
 
 // ----------------------------------------------------------------------------- VeLO hypernetwork

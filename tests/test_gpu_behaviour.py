@@ -49,6 +49,25 @@ def test_two_runs_are_bit_identical(kind):
         assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
 
 
+@pytest.mark.parametrize("groups", [2, 3, 16])
+def test_group_pipeline_is_bit_identical_to_one_stream(groups, monkeypatch):
+    # LOPT_GROUPS (read when the context is created) cuts the list into tensor groups whose HBM-bound passes run on
+    # the library's second stream beside the previous group's apply pass. The same kernels see the same tiles, so
+    # the results must not change by a single bit, on the default stream and on a stream of the caller's.
+    import torch
+    monkeypatch.setenv("LOPT_GROUPS", "1")
+    ref = _run("small_fc_lopt", 4)
+    monkeypatch.setenv("LOPT_GROUPS", str(groups))
+    out = _run("small_fc_lopt", 4)
+    for x, y in zip(ref, out):
+        assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        out2 = _run("small_fc_lopt", 4)
+    for x, y in zip(ref, out2):
+        assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
+
+
 @pytest.mark.parametrize("kind", ["small_fc_lopt", "velo"])
 def test_checkpoint_resume_is_bit_identical(kind):
     a = _run(kind, 6)
