@@ -58,6 +58,7 @@ struct Plan {
   uint64_t total_elems = 0;
   std::vector<size_t> state_bytes;
   uint64_t oLstmU = 0, oHNew = 0;   // VeLO scratch (floats)
+  uint64_t oCounters = 0;           // kMaxGroups ints: tile counters of the strip-form apply kernel
   uint64_t ws_floats = 0;
 };
 
@@ -66,6 +67,7 @@ struct Plan {
 struct lopt_ctx {
   lopt_config cfg;
   int device = 0;
+  int n_cu = 256;
   int HP = 0, F = 0, P = 0;
   float* d_weights = nullptr;      // the uploaded blob
   float* d_tail = nullptr;         // small_fc_lopt: padded W2 b2 W3 b3
@@ -149,6 +151,7 @@ void build_plan(const lopt_ctx* ctx, size_t n, const lopt_tensor_desc* d, Plan* 
   const uint64_t prep_floats = (uint64_t)(LOPT_D_VELO + 1) * HP + (uint64_t)HP * HP + HP + 2 * HP + 2;
   uint64_t off = 0;
   auto take = [&](uint64_t nfloats) { uint64_t o = off; off = align64(off + nfloats); return o; };
+  pl->oCounters = take(kMaxGroups);
   if (velo) {
     pl->oLstmU = take((uint64_t)n * kLstmInPad);
     pl->oHNew = take((uint64_t)n * ctx->cfg.lstm_hidden);
@@ -365,6 +368,7 @@ lopt_status lopt_create(const lopt_config* cfg, const float* weights_host, size_
     }                                                                                         \
   } while (0)
   CREATE_TRY(hipGetDevice(&ctx->device));
+  CREATE_TRY(hipDeviceGetAttribute(&ctx->n_cu, hipDeviceAttributeMultiprocessorCount, ctx->device));
   CREATE_TRY(hipMalloc((void**)&ctx->d_weights, n_weights * sizeof(float)));
   CREATE_TRY(hipMemcpy(ctx->d_weights, weights_host, n_weights * sizeof(float), hipMemcpyHostToDevice));
   CREATE_TRY(hipEventCreateWithFlags(&ctx->stage_ev, hipEventDisableTiming));
@@ -494,7 +498,7 @@ lopt_status lopt_init_state(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* des
   st = upload_tables(ctx, stream);
   if (st != LOPT_OK) return st;
   Launch L{ctx->d_tensors, ctx->d_tiles, ctx->d_rcitems, nullptr, (int)n, (int)ctx->plan.tiles.size(),
-           (int)ctx->plan.rcitems.size(), ctx->d_atiles, (int)ctx->plan.atiles.size(), 0, 0u};
+           (int)ctx->plan.rcitems.size(), ctx->d_atiles, (int)ctx->plan.atiles.size(), 0, 0u, nullptr, 0};
   StepArgs A = make_args(ctx, 0, 0.f, 0.f, (int)n);
   launch_fill_zero(L, A, stream);
   HIP_TRY(ctx, hipGetLastError());
@@ -528,7 +532,7 @@ lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, fl
   // workspace base rounded up to 256 bytes (lopt_state_bytes adds the slack)
   float* ws = (float*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255);
   Launch L{ctx->d_tensors, ctx->d_tiles, ctx->d_rcitems, ws, (int)n, (int)pl.tiles.size(), (int)pl.rcitems.size(),
-           ctx->d_atiles, (int)pl.atiles.size(), 0, 0u};
+           ctx->d_atiles, (int)pl.atiles.size(), 0, 0u, (int*)(ws + pl.oCounters), 2 * ctx->n_cu};
   StepArgs A = make_args(ctx, step, lr, weight_decay, (int)n);
   const bool mfma_ok = apply_mfma_available(A);
   // the strip-form kernel addresses a row pair with 32-bit byte offsets
@@ -574,6 +578,7 @@ lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, fl
       S.rcitems = L.rcitems + rc0; S.n_rcitems = rc1 - rc0;
       S.atiles = L.atiles + at0; S.n_atiles = at1 - at0;
       S.tensor0 = t0; S.n_tensors = t1 - t0;
+      S.apply_counter = L.apply_counter + g;
       return S;
     };
     auto passes_before_apply = [&](const Launch& S, hipStream_t s) {

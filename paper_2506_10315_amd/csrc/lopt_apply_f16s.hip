@@ -27,7 +27,7 @@
 //     layer-2 MFMAs, tile A, i+1   |  ReLU/split of tile B, round i+1
 //     layer-2 MFMAs, tile B, i+1   |  features of round i+2
 // and __builtin_amdgcn_sched_barrier(0) between the slices keeps the compiler from regrouping them.
-// Workgroup = 4 wavefronts = one apply tile of up to 128 rows x 128 columns.
+// Workgroup = 4 wavefronts; it works through apply tiles of up to kApplyRows rows x 128 columns, one at a time.
 #include <type_traits>
 
 #include "lopt_apply_common.h"
@@ -172,34 +172,21 @@ __device__ __forceinline__ void layer3_piece(const float4& w, const f32x16& h2a,
 
 template <bool RAW_RSQ>
 __global__ void __launch_bounds__(kBlock, 2) k_apply_f16s(const TensorDev* __restrict__ tensors,
-                                                          const ApplyTileDev* __restrict__ atiles,
-                                                          float* __restrict__ ws, StepArgs A,
-                                                          const float* __restrict__ tail) {
+                                                          const ApplyTileDev* __restrict__ atiles, int n_atiles,
+                                                          int* __restrict__ next_tile, float* __restrict__ ws,
+                                                          StepArgs A, const float* __restrict__ tail) {
   __shared__ StripLds L;
-  const ApplyTileDev at = atiles[blockIdx.x];
-  const TensorDev& T = tensors[at.tensor];
-  const int n = T.n, m = T.m;
+  __shared__ int s_tile;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int half = lane >> 5, l32 = lane & 31;
-  const float* __restrict__ prep = ws + T.oPrep;  // W1s[28][32] (normalization folded in), b1'[32]
-  const int col = at.c0 + wave * kStripCols + l32;
-  const bool col_ok = col < n;
-  const int r0 = at.r0, r1 = at.r0 + at.rows;
-  const float* __restrict__ rst = T.st + 4 * (size_t)T.padN;   // r_k[3][padm] then c_k[3][padn]
 
-  // ---- tables shared by the workgroup
-  {
-    const int t = threadIdx.x;
-    if (t < 192) L.w1row[t >> 5][t & 31] = prep[row_feat(t >> 5) * kH + (t & 31)];
-    else if (t < 224) L.b1[t - 192] = prep[kNF * kH + (t - 192)];
-    else if (t < 240) {
-      const int hf = (t >> 3) & 1, v2 = t & 7;
-      const float* w3g = tail + kH * kH + kH;
-      const int u0 = unit_of(2 * v2, hf), u1 = unit_of(2 * v2 + 1, hf);
-      L.w3[hf][v2] = make_float4(w3g[2 * u0], w3g[2 * u0 + 1], w3g[2 * u1], w3g[2 * u1 + 1]);
-    }
+  // ---- what does not depend on the tile: W3 table, packed weights, scalars
+  if (threadIdx.x < 16) {
+    const int hf = (threadIdx.x >> 3) & 1, v2 = threadIdx.x & 7;
+    const float* w3g = tail + kH * kH + kH;
+    const int u0 = unit_of(2 * v2, hf), u1 = unit_of(2 * v2 + 1, hf);
+    L.w3[hf][v2] = make_float4(w3g[2 * u0], w3g[2 * u0 + 1], w3g[2 * u1], w3g[2 * u1 + 1]);
   }
-
   Consts C;
   C.eps = A.eps_acc; C.lr = A.lr; C.wd = A.wd; C.exp_mult = A.exp_mult; C.step_mult = A.step_mult;
   C.b3d = tail[kH * kH + kH + 2 * kH]; C.b3m = tail[kH * kH + kH + 2 * kH + 1];
@@ -229,6 +216,30 @@ __global__ void __launch_bounds__(kBlock, 2) k_apply_f16s(const TensorDev* __res
 #pragma unroll
     for (int v = 0; v < 16; ++v) C.cb2[v] = tail[kH * kH + unit_of(v, half)];
   }
+  const unsigned one2 = 0x3C003C00u;   // fp16 (1.0, 1.0)
+  C.b_one_lo = pk8(half ? 0u : one2, 0u, 0u, 0u);
+  C.b_one_hi = pk8(half ? one2 : 0u, 0u, 0u, 0u);
+
+  // ---- tiles are handed out through a counter: a workgroup takes the next one when it is done with its last,
+  // so the launch is as many workgroups as fit on the chip and ends without a ragged last round
+  for (;;) {
+  if (threadIdx.x == 0) s_tile = atomicAdd(next_tile, 1);
+  __syncthreads();   // also: every wavefront is done with the previous tile's LDS tables
+  const int tile_id = s_tile;
+  if (tile_id >= n_atiles) break;
+  const ApplyTileDev at = atiles[tile_id];
+  const TensorDev& T = tensors[at.tensor];
+  const int n = T.n, m = T.m;
+  const float* __restrict__ prep = ws + T.oPrep;  // W1s[28][32] (normalization folded in), b1'[32]
+  const int col = at.c0 + wave * kStripCols + l32;
+  const bool col_ok = col < n;
+  const int r0 = at.r0, r1 = at.r0 + at.rows;
+  const float* __restrict__ rst = T.st + 4 * (size_t)T.padN;   // r_k[3][padm] then c_k[3][padn]
+  {
+    const int t = threadIdx.x;
+    if (t < 192) L.w1row[t >> 5][t & 31] = prep[row_feat(t >> 5) * kH + (t & 31)];
+    else if (t < 224) L.b1[t - 192] = prep[kNF * kH + (t - 192)];
+  }
   // ---- column part of layer 1's C operand for this lane's column: units unit_of(v, half), v = 0..15
   {
     float cf[6];
@@ -252,10 +263,6 @@ __global__ void __launch_bounds__(kBlock, 2) k_apply_f16s(const TensorDev* __res
   }
 #pragma unroll
   for (int i = 0; i < 10; ++i) C.sc[i] = ws[T.oScale + i];
-  const unsigned one2 = 0x3C003C00u;   // fp16 (1.0, 1.0)
-  C.b_one_lo = pk8(half ? 0u : one2, 0u, 0u, 0u);
-  C.b_one_hi = pk8(half ? one2 : 0u, 0u, 0u, 0u);
-
   __syncthreads();   // w1row, b1
   // ---- row part of the tile's rows -> LDS (thread: unit t & 31, rows (t >> 5), +8, ...); rows past the tile
   // hold zeros: the injection MFMA multiplies them by 0, and the pipeline's run-out rounds read them
@@ -451,18 +458,21 @@ __global__ void __launch_bounds__(kBlock, 2) k_apply_f16s(const TensorDev* __res
     for (int s = 0; s < kSets; ++s)   // update rows q + 2s, +1 (nothing is stored past the tile); features of round +2
       step(std::true_type{}, es[(s + 2) % kSets], q + 2 * s);
   }
+  }   // tile loop
 }
 
+// L.apply_counter must be zero when the kernel starts (k_finalize of the same sub-list clears it).
 void launch_apply_f16s(const Launch& L, const StepArgs& A, const WeightsDev& W, hipStream_t s) {
   if (L.n_atiles == 0) return;
+  const int grid = L.n_atiles < L.resident_wgs ? L.n_atiles : L.resident_wgs;
   // v_rsq_f32 treats inputs below the smallest normal float as zero; with eps_acc that small the kernel
   // takes the library reciprocal square root (which rescales such inputs) instead of the bare instruction
   if (A.eps_acc >= 1e-30f)
-    hipLaunchKernelGGL(k_apply_f16s<true>, dim3(L.n_atiles), dim3(kBlock), 0, s, L.tensors, L.atiles, L.ws, A,
-                       W.mlp_tail);
+    hipLaunchKernelGGL(k_apply_f16s<true>, dim3(grid), dim3(kBlock), 0, s, L.tensors, L.atiles, L.n_atiles,
+                       L.apply_counter, L.ws, A, W.mlp_tail);
   else
-    hipLaunchKernelGGL(k_apply_f16s<false>, dim3(L.n_atiles), dim3(kBlock), 0, s, L.tensors, L.atiles, L.ws, A,
-                       W.mlp_tail);
+    hipLaunchKernelGGL(k_apply_f16s<false>, dim3(grid), dim3(kBlock), 0, s, L.tensors, L.atiles, L.n_atiles,
+                       L.apply_counter, L.ws, A, W.mlp_tail);
 }
 
 }  // namespace lopt

@@ -290,12 +290,14 @@ void launch_accum_stats(const Launch& L, const StepArgs& A, hipStream_t s) {
 // One workgroup per tensor. Reduces every partial in a fixed order (double accumulation),
 // then writes s_f, the per-feature scale factors and the prepared first layer.
 __global__ void __launch_bounds__(kBlock) k_finalize(const TensorDev* __restrict__ tensors, float* __restrict__ ws,
-                                                     StepArgs A, WeightsDev W, float* __restrict__ lstm_u, int tensor0) {
+                                                     StepArgs A, WeightsDev W, float* __restrict__ lstm_u, int tensor0,
+                                                     int* __restrict__ apply_counter) {
   __shared__ double part[8][32];
   __shared__ double tot[48];
   __shared__ float s_stats[32], s_scale[32], s_tfeat[LOPT_N_TIME];
   const int ti = tensor0 + (int)blockIdx.x;
   const TensorDev& T = tensors[ti];
+  if (blockIdx.x == 0 && threadIdx.x == 0) *apply_counter = 0;   // the apply pass of this sub-list starts at its first tile
   if (threadIdx.x >= 64 && threadIdx.x < 64 + LOPT_N_TIME) {
     // time features tanh(t/x) (feature table of small_fc_lopt, row "Time Features")
     const double xs[LOPT_N_TIME] = {1, 3, 10, 30, 100, 300, 1000, 3000, 1e4, 3e4, 1e5};
@@ -394,7 +396,8 @@ __global__ void __launch_bounds__(kBlock) k_finalize(const TensorDev* __restrict
 
 void launch_finalize(const Launch& L, const StepArgs& A, const WeightsDev& W, float* lstm_u, hipStream_t s) {
   if (L.n_tensors == 0) return;
-  hipLaunchKernelGGL(k_finalize, dim3(L.n_tensors), dim3(kBlock), 0, s, L.tensors, L.ws, A, W, lstm_u, L.tensor0);
+  hipLaunchKernelGGL(k_finalize, dim3(L.n_tensors), dim3(kBlock), 0, s, L.tensors, L.ws, A, W, lstm_u, L.tensor0,
+                     L.apply_counter);
 }
 
 // ----------------------------------------------------------------------------- VeLO hypernetwork
