@@ -581,16 +581,18 @@ lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, fl
       S.apply_counter = L.apply_counter + g;
       return S;
     };
-    auto passes_before_apply = [&](const Launch& S, hipStream_t s) {
-      launch_rowcol_sums(S, A, s);
-      launch_rc_update(S, A, s);
+    // accumulator update + statistics + per-tensor finalize of one group: what its apply pass waits for
+    auto stats_passes = [&](const Launch& S, hipStream_t s) {
       launch_accum_stats(S, A, s);
       launch_finalize(S, A, ctx->W, ws + pl.oLstmU, s);
     };
     hipStream_t aux = ctx->aux_stream;
+    // the row/column pass reads only the gradients (4 of the step's 72 bytes per element): whole list, up front
+    launch_rowcol_sums(L, A, stream);
+    launch_rc_update(L, A, stream);
     HIP_TRY(ctx, hipEventRecord(ctx->ev_fork, stream));       // aux joins the caller's stream here ...
     HIP_TRY(ctx, hipStreamWaitEvent(aux, ctx->ev_fork, 0));
-    passes_before_apply(sub(0), stream);
+    stats_passes(sub(0), stream);
     for (int g = 0; g < G; ++g) {
       if (g + 1 < G) {
         // the next group's HBM-bound passes start when this group's are done, i.e. together with its apply pass
@@ -598,7 +600,7 @@ lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, fl
         HIP_TRY(ctx, hipStreamWaitEvent(aux, ctx->ev_start[g + 1], 0));
         Launch Sn = sub(g + 1);
         Sn.ballast_lds = ctx->shadow_lds;
-        passes_before_apply(Sn, aux);
+        stats_passes(Sn, aux);
         HIP_TRY(ctx, hipEventRecord(ctx->ev_pre[g + 1], aux));
       }
       launch_apply(sub(g));

@@ -21,7 +21,7 @@ constexpr int kStatsPerTensor = 32;
 constexpr int kLstmInPad = 48;    // LOPT_VELO_LSTM_IN rounded up
 constexpr int kLstmTensorsPerBlock = 8;
 #ifndef LOPT_APPLY_ROWS
-#define LOPT_APPLY_ROWS 64
+#define LOPT_APPLY_ROWS 128
 #endif
 constexpr int kApplyRows = LOPT_APPLY_ROWS;   // tile of the strip-form apply kernel: up to this many rows x 128 columns
 constexpr int kApplyCols = 128;
