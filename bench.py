@@ -24,6 +24,11 @@ HBM_PEAK_GBS = 8000.0
 MFMA_F32_PEAK_TFLOPS = 157.3      # fp32 matrix (= packed fp32 vector) peak
 MFMA_F16_PEAK_TFLOPS = 2500.0     # dense fp16/bf16 matrix peak
 
+# Vector-ALU instruction issue: 256 CUs x 4 SIMDs, one wave64 instruction per 4 cycles and SIMD, 2.4 GHz
+VALU_ISSUE_PEAK_GINST = 256 * 4 * 2.4 / 4          # 614.4 G wave-instructions/s
+# k_apply_f16s executes 316 vector instructions (20 of them MFMAs) per round of 64 elements (profiles/sq_counters_vit_b16.md)
+APPLY_F16S_INST_PER_ROUND = 316
+
 # Algorithmic work per element of the dominant pass:
 #   apply pass, small_fc_lopt hidden 32: MLP contraction 28*32 + 32*32 + 32*2 MACs = 3968 FLOP
 #   apply pass bytes: read g, p, M1..3, V (24 B) + write p (4 B) = 28 B
@@ -36,10 +41,10 @@ ACCUM_BYTES = 40
 # scaled by the factors a plain 256 MiB copy gives (2.0 / 1.0): see profiles/hbm_traffic_vit_b16.md.
 # Keyed by (config, pass); other configurations report null.
 MEASURED_TRAFFIC_BYTES = {
-    (2, "apply"): (1_027_000 * 2.0 + 338_200) * 1024,
-    (2, "accum_stats"): (1_024_000 * 2.0 + 1_353_000) * 1024,
-    (3, "apply"): (1_028_000 * 2.0 + 338_200) * 1024,
-    (3, "accum_stats"): (1_024_000 * 2.0 + 1_353_000) * 1024,
+    (2, "apply"): (1_084_192 * 2.0 + 338_366) * 1024,
+    (2, "accum_stats"): (1_020_355 * 2.0 + 1_353_160) * 1024,
+    (3, "apply"): (1_024_089 * 2.0 + 338_155) * 1024,
+    (3, "accum_stats"): (1_020_277 * 2.0 + 1_353_160) * 1024,
 }
 
 
@@ -179,6 +184,14 @@ def main():
                 "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE x2 + WRITE_SIZE, see profiles/)",
                 "avg_launch_ms": pass_ms[dominant], "pass_ms": pass_ms,
                 "ms_per_step_with_events": dt_prof / args.steps * 1e3}
+    if dominant == "apply" and optimizer == "small_fc_lopt" and variant in ("auto", "mfma_f16s"):
+        # what actually binds this kernel: vector-instruction issue (executed instructions, not algorithmic work)
+        ginst = APPLY_F16S_INST_PER_ROUND * (n_el / 64) / dur_s / 1e9
+        roofline["valu_issue"] = {"achieved": ginst, "peak": VALU_ISSUE_PEAK_GINST, "unit": "G wave-instructions/s",
+                                  "frac": ginst / VALU_ISSUE_PEAK_GINST,
+                                  "note": "executed vector instructions per 64 elements x rounds / launch time"}
+    roofline["timing_note"] = ("pass_ms / avg_launch_ms: second run of the same K steps with per-pass HIP events, every pass "
+                               "over the whole list on one stream (the tensor-group pipeline is off while events are on)")
     # every HBM-bound pass against the 8 TB/s roof (algorithmic bytes per element: 4 / 40 / 28)
     roofline["hbm_frac_by_pass"] = {
         name: (b * n_el / (pass_ms[name] * 1e-3) / 1e9) / HBM_PEAK_GBS
@@ -189,7 +202,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{'micro' if args.micro else 'config ' + str(args.config)}: {optimizer} on {wl.name} shapes "
                                f"({n} tensors, {n_el} fp32 elements), all tensors in one lopt_step",
-                   "optimizer": optimizer, "hidden": int(cfg.hidden)},
+                   "optimizer": optimizer, "hidden": int(cfg.hidden),
+                   "launch": "lopt_step defaults (tensor-group pipeline on two streams for large small_fc_lopt lists)"
+                             if not os.environ.get("LOPT_GROUPS") else "LOPT_GROUPS=" + os.environ["LOPT_GROUPS"]},
         "finite": finite,
         "roofline": roofline,
     }
