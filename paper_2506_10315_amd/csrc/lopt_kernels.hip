@@ -258,6 +258,81 @@ __device__ __forceinline__ void accum_tile(const TensorDev& T, const TileDev& ti
   }
 }
 
+// The same pass for tensors whose rows are 16-byte aligned (n % 4 == 0), which is nearly all of the work: a lane's
+// four columns are either all inside the tensor or all outside, so lanes past the last column sit the tile out
+// and nothing in the loop is predicated. The sums of squares are taken in the form that needs the fewest vector
+// instructions: (M_i rsqrt(V+eps))^2 = M_i^2 / (V+eps), (g a_i b_j)^2 = g^2 a_i^2 b_j^2 (squared row and column
+// factors are formed once per row / per tile), clip(g, +-0.1)^2 = min(g^2, 0.01). RAW_RCP: the bare v_rcp_f32 (it
+// treats inputs below the smallest normal float as zero, so the launcher asks for it only when eps_acc >= 1e-30).
+typedef float __attribute__((ext_vector_type(4))) f32x4v;
+typedef const f32x4v __attribute__((address_space(1)))* gcv4;
+typedef f32x4v __attribute__((address_space(1)))* gv4;
+
+template <bool RAW_RCP>
+__device__ __forceinline__ void accum_tile_vec(const TensorDev& T, const TileDev& tile, float* __restrict__ ws,
+                                               const StepArgs& A, float (&acc)[kNStat]) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = T.n, m = T.m;
+  const int col = tile.tj * kTileCols + 4 * lane;
+  if (col >= n) return;
+  const int r0 = tile.ti * T.TR;
+  const int r1 = min(r0 + T.TR, m);
+  float rc2[3][4];
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    const float4 c = *reinterpret_cast<const float4*>(ws + T.oRC + (size_t)k * T.padn + col);
+    rc2[k][0] = c.x * c.x; rc2[k][1] = c.y * c.y; rc2[k][2] = c.z * c.z; rc2[k][3] = c.w * c.w;
+  }
+  const size_t pN = T.padN;
+  const float b1 = A.mom_decay[0], b2 = A.mom_decay[1], b3 = A.mom_decay[2], b4 = A.rms_decay;
+  const float a1 = 1.0f - b1, a2 = 1.0f - b2, a3 = 1.0f - b3, a4 = 1.0f - b4;
+  const float eps = A.eps_acc;
+  const float clip2 = 0.1f * 0.1f;
+  for (int r = r0 + wave; r < r1; r += 4) {
+    const size_t ro = (size_t)r * n + col;   // a multiple of 4: every section starts 16-byte aligned
+    const f32x4v g4 = __builtin_nontemporal_load((gcv4)(T.g + ro));
+    const f32x4v p4 = __builtin_nontemporal_load((gcv4)(T.p + ro));
+    const f32x4v m1 = __builtin_nontemporal_load((gcv4)(T.st + ro));
+    const f32x4v m2 = __builtin_nontemporal_load((gcv4)(T.st + pN + ro));
+    const f32x4v m3 = __builtin_nontemporal_load((gcv4)(T.st + 2 * pN + ro));
+    const f32x4v v4 = __builtin_nontemporal_load((gcv4)(T.st + 3 * pN + ro));
+    float rr2[3];
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+      const float rr = ws[T.oRR + (size_t)k * T.padm + r];
+      rr2[k] = rr * rr;
+    }
+    f32x4v o1, o2, o3, ov;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float g = g4[e], p = p4[e];
+      const float g2 = g * g;
+      const float nm1 = b1 * m1[e] + a1 * g;
+      const float nm2 = b2 * m2[e] + a2 * g;
+      const float nm3 = b3 * m3[e] + a3 * g;
+      const float nv = b4 * v4[e] + a4 * g2;
+      o1[e] = nm1; o2[e] = nm2; o3[e] = nm3; ov[e] = nv;
+      const float s1 = nm1 * nm1, s2 = nm2 * nm2, s3 = nm3 * nm3;
+      const float rs2 = RAW_RCP ? __builtin_amdgcn_rcpf(nv + eps) : 1.0f / (nv + eps);
+      const float f0 = rr2[0] * rc2[0][e], f1 = rr2[1] * rc2[1][e], f2 = rr2[2] * rc2[2][e];
+      acc[0] += g2;
+      acc[1] += p * p;
+      acc[2] += s1; acc[3] += s2; acc[4] += s3;
+      acc[5] += nv * nv;
+      acc[6] += s1 * rs2; acc[7] += s2 * rs2; acc[8] += s3 * rs2;
+      acc[9] += rs2;
+      acc[10] += g2 * f0; acc[11] += g2 * f1; acc[12] += g2 * f2;
+      acc[13] += s1 * f0; acc[14] += s2 * f1; acc[15] += s3 * f2;
+      acc[16] += fminf(g2, clip2);
+    }
+    *(gv4)(T.st + ro) = o1;
+    *(gv4)(T.st + pN + ro) = o2;
+    *(gv4)(T.st + 2 * pN + ro) = o3;
+    *(gv4)(T.st + 3 * pN + ro) = ov;
+  }
+}
+
+template <bool RAW_RCP>
 __global__ void __launch_bounds__(kBlock) k_accum_stats(const TensorDev* __restrict__ tensors,
                                                         const TileDev* __restrict__ tiles, float* __restrict__ ws,
                                                         StepArgs A) {
@@ -267,7 +342,7 @@ __global__ void __launch_bounds__(kBlock) k_accum_stats(const TensorDev* __restr
   float acc[kNStat];
 #pragma unroll
   for (int q = 0; q < kNStat; ++q) acc[q] = 0.f;
-  if (T.vec) accum_tile<true>(T, tile, ws, A, acc);
+  if (T.vec) accum_tile_vec<RAW_RCP>(T, tile, ws, A, acc);
   else accum_tile<false>(T, tile, ws, A, acc);
   const int lt = tile.ti * T.nct + tile.tj;
   block_sum<kNStat>(acc, red, ws + T.oStatPart + (size_t)lt * kStatStride);
@@ -277,12 +352,17 @@ __global__ void __launch_bounds__(kBlock) k_accum_stats(const TensorDev* __restr
 hipError_t enable_ballast_lds() {
   hipError_t e = hipFuncSetAttribute((const void*)k_rowcol_sums, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
   if (e != hipSuccess) return e;
-  return hipFuncSetAttribute((const void*)k_accum_stats, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+  e = hipFuncSetAttribute((const void*)k_accum_stats<true>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute((const void*)k_accum_stats<false>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
 }
 
 void launch_accum_stats(const Launch& L, const StepArgs& A, hipStream_t s) {
   if (L.n_tiles == 0) return;
-  hipLaunchKernelGGL(k_accum_stats, dim3(L.n_tiles), dim3(kBlock), L.ballast_lds, s, L.tensors, L.tiles, L.ws, A);
+  if (A.eps_acc >= 1e-30f)
+    hipLaunchKernelGGL(k_accum_stats<true>, dim3(L.n_tiles), dim3(kBlock), L.ballast_lds, s, L.tensors, L.tiles, L.ws, A);
+  else
+    hipLaunchKernelGGL(k_accum_stats<false>, dim3(L.n_tiles), dim3(kBlock), L.ballast_lds, s, L.tensors, L.tiles, L.ws, A);
 }
 
 // ----------------------------------------------------------------------------- finalize
