@@ -372,7 +372,7 @@ lopt_status lopt_create(const lopt_config* cfg, const float* weights_host, size_
   CREATE_TRY(hipMalloc((void**)&ctx->d_weights, n_weights * sizeof(float)));
   CREATE_TRY(hipMemcpy(ctx->d_weights, weights_host, n_weights * sizeof(float), hipMemcpyHostToDevice));
   CREATE_TRY(hipEventCreateWithFlags(&ctx->stage_ev, hipEventDisableTiming));
-  if (cfg->kind == LOPT_SMALL_FC) {
+  {
     CREATE_TRY(hipStreamCreateWithFlags(&ctx->aux_stream, hipStreamNonBlocking));
     CREATE_TRY(enable_ballast_lds());
     if (const char* e = getenv("LOPT_SHADOW_LDS_KB")) ctx->shadow_lds = (unsigned)atoi(e) * 1024u;
@@ -550,8 +550,10 @@ lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, fl
   // ---- group pipeline: only where the apply pass is compute-bound (strip form), the list is large enough to
   // pay for the extra launches, and per-pass timing is off (its events assume one pass after the other)
   int G = 1;
-  if (strip_ok && ctx->aux_stream && !ctx->profiling) {
-    G = ctx->groups_override ? ctx->groups_override : pl.total_elems >= (256u << 20) ? 8 : pl.total_elems >= (32u << 20) ? 4 : 1;
+  const bool velo = ctx->cfg.kind == LOPT_VELO;
+  if (ctx->aux_stream && !ctx->profiling) {
+    if (strip_ok) G = ctx->groups_override ? ctx->groups_override : pl.total_elems >= (256u << 20) ? 8 : pl.total_elems >= (32u << 20) ? 4 : 1;
+    else if (velo) G = ctx->groups_override ? ctx->groups_override : 1;
     if ((size_t)G > n) G = (int)n;
   }
   if (G > 1) {
@@ -585,6 +587,10 @@ lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, fl
     auto stats_passes = [&](const Launch& S, hipStream_t s) {
       launch_accum_stats(S, A, s);
       launch_finalize(S, A, ctx->W, ws + pl.oLstmU, s);
+      if (velo) {
+        launch_velo_lstm(S, A, ctx->W, ws + pl.oLstmU, ws + pl.oHNew, s);
+        launch_velo_head(S, A, ctx->W, ws + pl.oHNew, s);
+      }
     };
     hipStream_t aux = ctx->aux_stream;
     // the row/column pass reads only the gradients (4 of the step's 72 bytes per element): whole list, up front
@@ -599,7 +605,7 @@ lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, fl
         HIP_TRY(ctx, hipEventRecord(ctx->ev_start[g + 1], stream));
         HIP_TRY(ctx, hipStreamWaitEvent(aux, ctx->ev_start[g + 1], 0));
         Launch Sn = sub(g + 1);
-        Sn.ballast_lds = ctx->shadow_lds;
+        Sn.ballast_lds = velo ? 0u : ctx->shadow_lds;
         stats_passes(Sn, aux);
         HIP_TRY(ctx, hipEventRecord(ctx->ev_pre[g + 1], aux));
       }

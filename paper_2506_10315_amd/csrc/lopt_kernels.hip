@@ -574,7 +574,11 @@ void launch_velo_lstm(const Launch& L, const StepArgs& A, const WeightsDev& W, c
   const int stride = kLstmInPad + ((A.HL + 3) & ~3);
   const int nw = A.HL <= 512 ? 16 : 8;   // wavefronts per workgroup = ways the reduction is split (LDS stays < 64 KB)
   size_t shmem = (size_t)(kLstmTensorsPerBlock * stride + nw * kLstmTensorsPerBlock * 64) * sizeof(float);
-  hipLaunchKernelGGL(k_velo_lstm, grid, dim3(64 * nw), shmem, s, L.tensors, A, W, lstm_u, h_new);
+  // a sub-list starts at tensor L.tensor0: the kernel indexes tensors, inputs and outputs from there
+  StepArgs As = A;
+  As.n_tensors = L.n_tensors;
+  hipLaunchKernelGGL(k_velo_lstm, grid, dim3(64 * nw), shmem, s, L.tensors + L.tensor0, As, W,
+                     lstm_u + (size_t)L.tensor0 * kLstmInPad, h_new + (size_t)L.tensor0 * A.HL);
 }
 
 // Partial matrix-vector product for the hypernetwork head: out[w][c0 + 64 c + lane] = sum over rows
@@ -670,7 +674,8 @@ void launch_velo_head(const Launch& L, const StepArgs& A, const WeightsDev& W, c
   int nw = 16;  // wavefronts per workgroup = ways the reductions are split; bounded by 48 KB of partials
   while (nw > 1 && (size_t)nw * W64 * sizeof(float) > 48 * 1024) nw >>= 1;
   size_t shmem = (size_t)(A.HL + A.K + nw * W64) * sizeof(float);
-  hipLaunchKernelGGL(k_velo_head, dim3(L.n_tensors), dim3(64 * nw), shmem, s, L.tensors, L.ws, A, W, h_new);
+  hipLaunchKernelGGL(k_velo_head, dim3(L.n_tensors), dim3(64 * nw), shmem, s, L.tensors + L.tensor0, L.ws, A, W,
+                     h_new + (size_t)L.tensor0 * A.HL);
 }
 
 }  // namespace lopt
