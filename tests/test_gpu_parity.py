@@ -102,3 +102,17 @@ def test_degenerate_gradients(kind):
 
     worst = Hn.run_free(Degenerate(107, _specs(shapes)), cfg, w, 3)
     assert np.isfinite(worst["param"])
+
+
+@pytest.mark.parametrize("kind", ["small_fc_lopt", "velo"])
+def test_tiny_eps_acc_takes_the_library_reciprocal_roots(kind):
+    # With eps_acc below 1e-30 the kernels must not use the bare reciprocal / reciprocal-square-root instructions
+    # (they flush inputs below the smallest normal float): separate instantiations, exercised here with eps_acc = 0
+    # and eps_acc = 1e-38 on gradients that keep every accumulator positive.
+    for eps in (0.0, 1e-38):
+        cfg = Hn.make_cfg(kind) if kind == "small_fc_lopt" else Hn.make_cfg(kind, lstm_hidden=32, n_bank=16)
+        cfg.eps_acc = eps
+        w = Hn.random_weights(cfg, 5)
+        worst = Hn.run_free(Hn.Case(108, _specs([(130, 260), (64, 256), (300,), (70, 36)]), "gauss_logscale"), cfg, w, 3,
+                            lr_fn=lambda t: 0.9, wd=0.01)
+        assert worst["param"] <= Hn.TOL_PARAM
