@@ -19,7 +19,6 @@ constexpr int kRcStride = 12;     // floats per block in the row/column partials
 constexpr int kNStat = 17;        // per-element statistics accumulated per tile
 constexpr int kStatsPerTensor = 32;
 constexpr int kLstmInPad = 48;    // LOPT_VELO_LSTM_IN rounded up
-constexpr int kLstmTensorsPerBlock = 8;
 #ifndef LOPT_APPLY_ROWS
 #define LOPT_APPLY_ROWS 128
 #endif

@@ -482,87 +482,98 @@ void launch_finalize(const Launch& L, const StepArgs& A, const WeightsDev& W, fl
 
 // ----------------------------------------------------------------------------- VeLO hypernetwork
 
-// One LSTM-cell step for a group of kLstmTensorsPerBlock tensors and a slab of kLstmUnits hidden units.
-// A workgroup's 64 gate columns are (gate g = lane / 16, unit u0 + lane % 16); the reduction over the
-// 45 + H_L inputs is split across the workgroup's wavefronts (8 or 16) and finished through LDS, then one thread
-// per (tensor, unit) applies the cell equations. Inputs u and the previous h sit in LDS.
+// One LSTM-cell step for all tensors: Z[T, 4 H_L] = [u | h_prev] [Wx ; Wh] is a dense contraction and runs on the
+// matrix cores in fp32 (v_mfma_f32_32x32x2_f32: exact fp32 products, fp32 accumulation). A workgroup owns 32 tensors x
+// 16 hidden units (two 32-column MFMA tiles of 8 units x 4 gates); its four wavefronts split the 48 + H_L input slots
+// and meet in LDS in a fixed order; one thread per (tensor, unit pair) then applies the cell equations.
+// Operands go from global memory straight into the MFMA layout: lane (k-half, t) holds input slot 2p + k-half of tensor
+// t (A operand) and of column (gate, unit) = (lane%32 / 8, u0 + 8 tile + lane%8) (B operand). Loads are unconditional
+// (clamped to a valid row, multiplied by 0 where a slot carries nothing: the padding slots 45..47, slots past H_L,
+// tensors or units past the end), sixteen slot pairs = 48 loads in flight per wavefront: the kernel is bound by the
+// latency of those loads, not by arithmetic.
+constexpr int kLstmTensors = 32;
 constexpr int kLstmUnits = 16;
+constexpr int kLstmPairsPerTrip = 16;
+typedef float f32x16_l __attribute__((ext_vector_type(16)));
 
-__global__ void __launch_bounds__(1024) k_velo_lstm(const TensorDev* __restrict__ tensors, StepArgs A, WeightsDev W,
+__global__ void __launch_bounds__(kBlock) k_velo_lstm(const TensorDev* __restrict__ tensors, StepArgs A, WeightsDev W,
                                                       const float* __restrict__ lstm_u, float* __restrict__ h_new) {
-  extern __shared__ float sh[];  // x[kLstmTensorsPerBlock][kLstmInPad + HLp] then zpart[nw][kLstmTensorsPerBlock][64]
-  const int HL = A.HL;
-  const int stride = kLstmInPad + ((HL + 3) & ~3);
-  float* zpart = sh + kLstmTensorsPerBlock * stride;
-  const int t0 = blockIdx.x * kLstmTensorsPerBlock;
-  const int nt = min(kLstmTensorsPerBlock, A.n_tensors - t0);
-  for (int i = threadIdx.x; i < kLstmTensorsPerBlock * stride; i += blockDim.x) {
-    const int tt = i / stride, k = i - tt * stride;
-    float v = 0.f;
-    if (tt < nt) {
-      if (k < kLstmInPad) v = lstm_u[(size_t)(t0 + tt) * kLstmInPad + k];
-      else if (k - kLstmInPad < HL) {
-        const TensorDev& T = tensors[t0 + tt];
-        v = T.st[4 * (size_t)T.padN + 3 * (size_t)T.padm + 3 * (size_t)T.padn + (k - kLstmInPad)];
-      }
-    }
-    sh[i] = v;
-  }
-  __syncthreads();
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-  const int gI = lane >> 4, u = blockIdx.y * kLstmUnits + (lane & 15);
-  const bool live = u < HL;
-  const int G = 4 * HL;
-  const size_t colw = (size_t)gI * HL + (live ? u : 0);
-  float z[kLstmTensorsPerBlock];
+  __shared__ float part[4][2][32][32];   // [wavefront][column tile][tensor][column]: 32 KB
+  const int HL = A.HL, G = 4 * HL;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int khalf = lane >> 5, l32 = lane & 31;
+  const int t0 = blockIdx.x * kLstmTensors, u0 = blockIdx.y * kLstmUnits;
+  // A side: the tensor of this lane (clamped: rows past the list compute on the last tensor and are dropped)
+  const int tA = min(t0 + l32, A.n_tensors - 1);
+  const TensorDev& T = tensors[tA];
+  const float* __restrict__ hsrc = T.st + 4 * (size_t)T.padN + 3 * (size_t)T.padm + 3 * (size_t)T.padn;
+  const float* __restrict__ usrc = lstm_u + (size_t)tA * kLstmInPad;
+  // B side: the two columns of this lane
+  const int gate = l32 >> 3;
+  const int ua = min(u0 + (l32 & 7), HL - 1), ub = min(u0 + 8 + (l32 & 7), HL - 1);
+  const size_t cola = (size_t)gate * HL + ua, colb = (size_t)gate * HL + ub;
+
+  f32x16_l acc0, acc1;
 #pragma unroll
-  for (int tt = 0; tt < kLstmTensorsPerBlock; ++tt) z[tt] = 0.f;
-  // rows of [Wx ; Wh] handled by this wavefront: w, w+nw, ...; four rows (independent loads) per trip
-  const int nrows = LOPT_VELO_LSTM_IN + HL;
-  for (int kb = wave; kb < nrows; kb += 4 * nw) {
-    float w[4];
-    int kk[4];
+  for (int v = 0; v < 16; ++v) { acc0[v] = 0.f; acc1[v] = 0.f; }
+  // slot pairs of this wavefront; slots 0..47 are u (45 used), slots 48.. are h_prev; 48 is even, so a pair never straddles
+  const int n_pairs = (kLstmInPad + HL + 1) / 2;
+  const int per_wave = (n_pairs + 3) / 4;
+  const int p_begin = wave * per_wave, p_end = min(p_begin + per_wave, n_pairs);
+  for (int pb = p_begin; pb < p_end; pb += kLstmPairsPerTrip) {
+    float a[kLstmPairsPerTrip], b0[kLstmPairsPerTrip], b1[kLstmPairsPerTrip];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int k = kb + nw * j;
-      kk[j] = k;
-      w[j] = 0.f;
-      if (k < nrows && live)
-        w[j] = k < LOPT_VELO_LSTM_IN ? W.Wx[(size_t)k * G + colw] : W.Wh[(size_t)(k - LOPT_VELO_LSTM_IN) * G + colw];
+    for (int j = 0; j < kLstmPairsPerTrip; ++j) {
+      const int p = pb + j < p_end ? pb + j : p_end - 1;   // a repeated pair is multiplied by 0 below
+      const int k = 2 * p + khalf;
+      const bool isu = 2 * p < kLstmInPad;                  // wave-uniform
+      const int ku = k < LOPT_VELO_LSTM_IN ? k : LOPT_VELO_LSTM_IN - 1;
+      const int kh = k - kLstmInPad;
+      const int khc = kh < 0 ? 0 : kh < HL ? kh : HL - 1;
+      const float keep = (pb + j < p_end && (isu ? k < LOPT_VELO_LSTM_IN : kh < HL)) ? 1.f : 0.f;
+      const float* __restrict__ wrow = isu ? W.Wx + (size_t)ku * G : W.Wh + (size_t)khc * G;
+      a[j] = (isu ? usrc[ku] : hsrc[khc]) * keep;
+      b0[j] = wrow[cola];
+      b1[j] = wrow[colb];
     }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      if (kk[j] < nrows) {
-        const int xi = kk[j] < LOPT_VELO_LSTM_IN ? kk[j] : kLstmInPad + (kk[j] - LOPT_VELO_LSTM_IN);
-#pragma unroll
-        for (int tt = 0; tt < kLstmTensorsPerBlock; ++tt) z[tt] += sh[tt * stride + xi] * w[j];
-      }
+    for (int j = 0; j < kLstmPairsPerTrip; ++j) {
+      acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a[j], b0[j], acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a[j], b1[j], acc1, 0, 0, 0);
     }
   }
+  // accumulator register v of lane (k-half, c) is row 8 (v / 4) + 4 k-half + v % 4, column c
 #pragma unroll
-  for (int tt = 0; tt < kLstmTensorsPerBlock; ++tt) zpart[(wave * kLstmTensorsPerBlock + tt) * 64 + lane] = z[tt];
+  for (int v = 0; v < 16; ++v) {
+    const int row = 8 * (v >> 2) + 4 * khalf + (v & 3);
+    part[wave][0][row][l32] = acc0[v];
+    part[wave][1][row][l32] = acc1[v];
+  }
   __syncthreads();
-  if (threadIdx.x < kLstmTensorsPerBlock * kLstmUnits) {
-    const int tt = threadIdx.x / kLstmUnits, uu = threadIdx.x % kLstmUnits;
-    const int unit = blockIdx.y * kLstmUnits + uu;
-    if (tt < nt && unit < HL) {
-      float zz[4];
+  {
+    const int tt = threadIdx.x >> 3, uu = threadIdx.x & 7;
+    if (t0 + tt < A.n_tensors) {
+      const TensorDev& Tt = tensors[t0 + tt];
+      float* cl = Tt.st + 4 * (size_t)Tt.padN + 3 * (size_t)Tt.padm + 3 * (size_t)Tt.padn + Tt.padH;
 #pragma unroll
-      for (int g2 = 0; g2 < 4; ++g2) {
-        const int c = g2 * 16 + uu;
-        float a = W.b[g2 * HL + unit];
-        for (int w = 0; w < nw; ++w) a += zpart[(w * kLstmTensorsPerBlock + tt) * 64 + c];
-        zz[g2] = a;
+      for (int tile = 0; tile < 2; ++tile) {
+        const int unit = u0 + 8 * tile + uu;
+        if (unit < HL) {
+          float zz[4];
+#pragma unroll
+          for (int g2 = 0; g2 < 4; ++g2) {
+            const int c = g2 * 8 + uu;
+            zz[g2] = W.b[g2 * HL + unit] + ((part[0][tile][tt][c] + part[1][tile][tt][c]) + (part[2][tile][tt][c] + part[3][tile][tt][c]));
+          }
+          const float ig = 1.f / (1.f + expf(-zz[0]));
+          const float fg = 1.f / (1.f + expf(-zz[1]));
+          const float gg = tanhf(zz[2]);
+          const float og = 1.f / (1.f + expf(-zz[3]));
+          const float c = fg * cl[unit] + ig * gg;
+          cl[unit] = c;
+          h_new[(size_t)(t0 + tt) * HL + unit] = og * tanhf(c);
+        }
       }
-      const TensorDev& T = tensors[t0 + tt];
-      float* cl = T.st + 4 * (size_t)T.padN + 3 * (size_t)T.padm + 3 * (size_t)T.padn + T.padH;
-      const float ig = 1.f / (1.f + expf(-zz[0]));
-      const float fg = 1.f / (1.f + expf(-zz[1]));
-      const float gg = tanhf(zz[2]);
-      const float og = 1.f / (1.f + expf(-zz[3]));
-      const float c = fg * cl[unit] + ig * gg;
-      cl[unit] = c;
-      h_new[(size_t)(t0 + tt) * HL + unit] = og * tanhf(c);
     }
   }
 }
@@ -570,14 +581,11 @@ __global__ void __launch_bounds__(1024) k_velo_lstm(const TensorDev* __restrict_
 void launch_velo_lstm(const Launch& L, const StepArgs& A, const WeightsDev& W, const float* lstm_u, float* h_new,
                       hipStream_t s) {
   if (L.n_tensors == 0) return;
-  dim3 grid((L.n_tensors + kLstmTensorsPerBlock - 1) / kLstmTensorsPerBlock, (A.HL + kLstmUnits - 1) / kLstmUnits);
-  const int stride = kLstmInPad + ((A.HL + 3) & ~3);
-  const int nw = A.HL <= 512 ? 16 : 8;   // wavefronts per workgroup = ways the reduction is split (LDS stays < 64 KB)
-  size_t shmem = (size_t)(kLstmTensorsPerBlock * stride + nw * kLstmTensorsPerBlock * 64) * sizeof(float);
+  dim3 grid((L.n_tensors + kLstmTensors - 1) / kLstmTensors, (A.HL + kLstmUnits - 1) / kLstmUnits);
   // a sub-list starts at tensor L.tensor0: the kernel indexes tensors, inputs and outputs from there
   StepArgs As = A;
   As.n_tensors = L.n_tensors;
-  hipLaunchKernelGGL(k_velo_lstm, grid, dim3(64 * nw), shmem, s, L.tensors + L.tensor0, As, W,
+  hipLaunchKernelGGL(k_velo_lstm, grid, dim3(kBlock), 0, s, L.tensors + L.tensor0, As, W,
                      lstm_u + (size_t)L.tensor0 * kLstmInPad, h_new + (size_t)L.tensor0 * A.HL);
 }
 
