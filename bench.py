@@ -29,7 +29,7 @@ VALU_ISSUE_PEAK_GINST = 256 * 4 * 2.4 / 4          # 614.4 G wave-instructions/s
 # k_apply_f16s executes 316 vector instructions (20 of them MFMAs) per round of 64 elements (profiles/sq_counters_vit_b16.md)
 APPLY_F16S_INST_PER_ROUND = 316
 
-# Algorithmic work per element of the dominant pass (DESIGN.md "Roofline accounting"):
+# Algorithmic work per element of the dominant pass:
 #   apply pass, small_fc_lopt hidden 32: MLP contraction 28*32 + 32*32 + 32*2 MACs = 3968 FLOP
 #   apply pass bytes: read g, p, M1..3, V (24 B) + write p (4 B) = 28 B
 #   accum_stats pass bytes: read g, p, M1..3, V (24 B) + write M1..3, V (16 B) = 40 B
