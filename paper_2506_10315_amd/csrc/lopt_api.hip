@@ -552,7 +552,7 @@ lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, fl
   int G = 1;
   const bool velo = ctx->cfg.kind == LOPT_VELO;
   if (ctx->aux_stream && !ctx->profiling) {
-    if (strip_ok) G = ctx->groups_override ? ctx->groups_override : pl.total_elems >= (256u << 20) ? 8 : pl.total_elems >= (32u << 20) ? 4 : 1;
+    if (strip_ok) G = ctx->groups_override ? ctx->groups_override : pl.total_elems >= (1024u << 20) ? 16 : pl.total_elems >= (256u << 20) ? 8 : pl.total_elems >= (32u << 20) ? 4 : 1;
     else if (velo) G = ctx->groups_override ? ctx->groups_override : 1;
     if ((size_t)G > n) G = (int)n;
   }

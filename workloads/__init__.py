@@ -156,7 +156,7 @@ def micro_workload(name: str, optimizer: str = "small_fc_lopt") -> Workload:
 
 
 def get_workload(config_id: int, optimizer: str | None = None) -> Workload:
-    """The five benchmark configurations (config 4 exists for both optimizers)."""
+    """The five benchmark configurations (configs 4 and 5 take either optimizer; 5 defaults to VeLO)."""
     if config_id == 1:
         return Workload(1, "toy3", "small_fc_lopt", config1_shapes(), 10, "gauss_fixed")
     if config_id == 2:
@@ -168,7 +168,7 @@ def get_workload(config_id: int, optimizer: str | None = None) -> Workload:
         return Workload(4, "gpt2_medium", optimizer or "small_fc_lopt", gpt2_medium_shapes(), 50,
                         "student_t3")
     if config_id == 5:
-        return Workload(5, "llama_1p3b_plus_tiny", "velo", llama_1p3b_shapes(), 20, "gauss_logscale")
+        return Workload(5, "llama_1p3b_plus_tiny", optimizer or "velo", llama_1p3b_shapes(), 20, "gauss_logscale")
     raise ValueError(f"unknown config {config_id}")
 
 
