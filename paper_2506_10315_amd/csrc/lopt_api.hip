@@ -136,6 +136,25 @@ lopt_status check_descs(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* d) {
   return LOPT_OK;
 }
 
+// Number of tensor groups of the two-stream pipeline for a list of `total` elements (0 override = by size).
+int planned_groups(int override_g, uint64_t total, size_t n) {
+  int G = override_g ? override_g : total >= (1024u << 20) ? 16 : total >= (256u << 20) ? 8 : total >= (32u << 20) ? 4 : 1;
+  if ((size_t)G > n) G = (int)n;
+  return G < 1 ? 1 : G;
+}
+
+// Contiguous tensor ranges [bound[g], bound[g+1]) of about equal element count.
+void group_bounds(const lopt_tensor_desc* d, size_t n, int G, uint64_t total, int* bound) {
+  uint64_t cum = 0;
+  int g = 1;
+  bound[0] = 0;
+  for (size_t i = 0; i < n && g < G; ++i) {
+    cum += (uint64_t)d[i].rows * (uint64_t)d[i].cols;
+    if (cum * (uint64_t)G >= total * (uint64_t)g && (int)i + 1 > bound[g - 1]) bound[g++] = (int)i + 1;
+  }
+  while (g <= G) bound[g++] = (int)n;
+}
+
 // Lay out tiles, row/column blocks and workspace regions for a tensor list.
 void build_plan(const lopt_ctx* ctx, size_t n, const lopt_tensor_desc* d, Plan* pl) {
   pl->descs.assign(d, d + n);
@@ -156,6 +175,23 @@ void build_plan(const lopt_ctx* ctx, size_t n, const lopt_tensor_desc* d, Plan* 
     pl->oLstmU = take((uint64_t)n * kLstmInPad);
     pl->oHNew = take((uint64_t)n * ctx->cfg.lstm_hidden);
   }
+  // Apply tiles get shorter towards the end of every tensor group of the pipeline (a single group if it is off): the
+  // strip apply kernel hands tiles out in table order, so the last tiles of a launch decide how long the chip idles
+  // while the final workgroups finish (a 128-row tile is about 90 us of work, a 32-row tile a quarter of that).
+  uint64_t total = 0;
+  for (size_t i = 0; i < n; ++i) total += (uint64_t)d[i].rows * (uint64_t)d[i].cols;
+  const int G_plan = ctx->cfg.kind == LOPT_SMALL_FC ? planned_groups(ctx->groups_override, total, n) : 1;
+  int gbound[kMaxGroups + 1];
+  group_bounds(d, n, G_plan, total, gbound);
+  std::vector<uint64_t> gtotal(G_plan, 0), gbefore(n, 0);
+  for (int g = 0; g < G_plan; ++g)
+    for (int i = gbound[g]; i < gbound[g + 1]; ++i) {
+      gbefore[i] = gtotal[g];
+      gtotal[g] += (uint64_t)d[i].rows * (uint64_t)d[i].cols;
+    }
+  std::vector<int> group_of(n, 0);
+  for (int g = 0; g < G_plan; ++g)
+    for (int i = gbound[g]; i < gbound[g + 1]; ++i) group_of[i] = g;
   // Small parameter sets: with the standard 64-row tiles there may be fewer tiles than the chip has workgroup
   // slots (256 CUs x 2..8), so the tile height is halved until the list yields about 2048 tiles or reaches 8 rows.
   uint64_t std_tiles = 0;
@@ -189,12 +225,19 @@ void build_plan(const lopt_ctx* ctx, size_t n, const lopt_tensor_desc* d, Plan* 
     for (int b = 0; b < T.nrblk; ++b) pl->rcitems.push_back(RcItemDev{(int)i, 0, b, 0});
     for (int b = 0; b < T.ncblk; ++b) pl->rcitems.push_back(RcItemDev{(int)i, 1, b, 0});
     // apply tiles: up to kApplyRows x kApplyCols, shorter for small lists like the statistics tiles
-    const int AR = kApplyRows / shrink;
     pl->atile0[i] = (int)pl->atiles.size();
     pl->total_elems += N;
-    for (int ar0 = 0; ar0 < m; ar0 += AR)
-      for (int ac0 = 0; ac0 < nn; ac0 += kApplyCols)
-        pl->atiles.push_back(ApplyTileDev{(int)i, ar0, ac0, m - ar0 < AR ? m - ar0 : AR});
+    for (int ar0 = 0; ar0 < m;) {
+      // position of this row block inside its group: full height for the first 70 %, half to 88 %, a quarter after
+      const uint64_t pos = gbefore[i] + (uint64_t)ar0 * (uint64_t)nn, gt = gtotal[group_of[i]];
+      int AR = kApplyRows / shrink;
+      if (pos * 100 >= gt * 88) AR /= 4;
+      else if (pos * 100 >= gt * 70) AR /= 2;
+      if (AR < 8) AR = 8;
+      const int rows = m - ar0 < AR ? m - ar0 : AR;
+      for (int ac0 = 0; ac0 < nn; ac0 += kApplyCols) pl->atiles.push_back(ApplyTileDev{(int)i, ar0, ac0, rows});
+      ar0 += rows;
+    }
     T.oRowPart = take((uint64_t)T.nct * m);
     T.oColPart = take((uint64_t)T.nrt * nn);
     T.oRR = take(3ull * T.padm);
@@ -552,23 +595,13 @@ lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, fl
   int G = 1;
   const bool velo = ctx->cfg.kind == LOPT_VELO;
   if (ctx->aux_stream && !ctx->profiling) {
-    if (strip_ok) G = ctx->groups_override ? ctx->groups_override : pl.total_elems >= (1024u << 20) ? 16 : pl.total_elems >= (256u << 20) ? 8 : pl.total_elems >= (32u << 20) ? 4 : 1;
-    else if (velo) G = ctx->groups_override ? ctx->groups_override : 1;
-    if ((size_t)G > n) G = (int)n;
+    if (strip_ok) G = planned_groups(ctx->groups_override, pl.total_elems, n);
+    else if (velo && ctx->groups_override) G = planned_groups(ctx->groups_override, pl.total_elems, n);
   }
   if (G > 1) {
     // contiguous tensor ranges of about equal element count
     int bound[kMaxGroups + 1];
-    {
-      uint64_t cum = 0;
-      int g = 1;
-      bound[0] = 0;
-      for (size_t i = 0; i < n && g < G; ++i) {
-        cum += (uint64_t)descs[i].rows * (uint64_t)descs[i].cols;
-        if (cum * (uint64_t)G >= pl.total_elems * (uint64_t)g && (int)i + 1 > bound[g - 1]) bound[g++] = (int)i + 1;
-      }
-      while (g <= G) bound[g++] = (int)n;
-    }
+    group_bounds(descs, n, G, pl.total_elems, bound);
     auto sub = [&](int g) {
       const int t0 = bound[g], t1 = bound[g + 1];
       Launch S = L;
