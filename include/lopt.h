@@ -116,8 +116,7 @@ size_t lopt_weights_count(const lopt_config* cfg);
  *   LOPT_APPLY = valu | mfma_f32 | mfma_f16x3 | mfma_f16s   apply kernel for hidden width 32
  *                (default mfma_f16s: split-fp16 matrix cores, column strips, software-pipelined)
  *   LOPT_GROUPS = 1..16   number of tensor groups of the two-stream pipeline (default by list size;
- *                1 = every pass over the whole list, one after the other, on the caller's stream)
- *   LOPT_SHADOW_LDS_KB    unused LDS requested by the streaming passes that run beside an apply pass */
+ *                1 = every pass over the whole list, one after the other, on the caller's stream) */
 lopt_status lopt_create(const lopt_config* cfg, const float* weights_host, size_t n_weights,
                         lopt_ctx** out);
 

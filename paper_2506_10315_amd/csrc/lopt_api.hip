@@ -92,8 +92,6 @@ struct lopt_ctx {
   // Group pipeline (small_fc_lopt, strip-form apply): the tensor list is cut into groups; the HBM-bound passes of
   // group g+1 run on `aux_stream` while the compute-bound apply pass of group g runs on the caller's stream.
   int groups_override = 0;         // LOPT_GROUPS in the environment at create (0 = choose by size)
-  unsigned shadow_lds = 72 * 1024; // LDS ballast of the streaming passes that run beside an apply pass: at most one of
-                                   // their workgroups fits on a CU next to the apply pass's two (LOPT_SHADOW_LDS_KB)
   hipStream_t aux_stream = nullptr;
   hipEvent_t ev_fork = nullptr;
   std::vector<hipEvent_t> ev_start, ev_pre;   // per group: "previous group's passes are enqueued" / "this group's passes are done"
@@ -417,8 +415,6 @@ lopt_status lopt_create(const lopt_config* cfg, const float* weights_host, size_
   CREATE_TRY(hipEventCreateWithFlags(&ctx->stage_ev, hipEventDisableTiming));
   {
     CREATE_TRY(hipStreamCreateWithFlags(&ctx->aux_stream, hipStreamNonBlocking));
-    CREATE_TRY(enable_ballast_lds());
-    if (const char* e = getenv("LOPT_SHADOW_LDS_KB")) ctx->shadow_lds = (unsigned)atoi(e) * 1024u;
     CREATE_TRY(hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming));
     for (int g = 0; g < kMaxGroups; ++g) {
       hipEvent_t a = nullptr, b = nullptr;
@@ -541,7 +537,7 @@ lopt_status lopt_init_state(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* des
   st = upload_tables(ctx, stream);
   if (st != LOPT_OK) return st;
   Launch L{ctx->d_tensors, ctx->d_tiles, ctx->d_rcitems, nullptr, (int)n, (int)ctx->plan.tiles.size(),
-           (int)ctx->plan.rcitems.size(), ctx->d_atiles, (int)ctx->plan.atiles.size(), 0, 0u, nullptr, 0};
+           (int)ctx->plan.rcitems.size(), ctx->d_atiles, (int)ctx->plan.atiles.size(), 0, nullptr, 0};
   StepArgs A = make_args(ctx, 0, 0.f, 0.f, (int)n);
   launch_fill_zero(L, A, stream);
   HIP_TRY(ctx, hipGetLastError());
@@ -575,7 +571,7 @@ lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, fl
   // workspace base rounded up to 256 bytes (lopt_state_bytes adds the slack)
   float* ws = (float*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255);
   Launch L{ctx->d_tensors, ctx->d_tiles, ctx->d_rcitems, ws, (int)n, (int)pl.tiles.size(), (int)pl.rcitems.size(),
-           ctx->d_atiles, (int)pl.atiles.size(), 0, 0u, (int*)(ws + pl.oCounters), 2 * ctx->n_cu};
+           ctx->d_atiles, (int)pl.atiles.size(), 0, (int*)(ws + pl.oCounters), 2 * ctx->n_cu};
   StepArgs A = make_args(ctx, step, lr, weight_decay, (int)n);
   const bool mfma_ok = apply_mfma_available(A);
   // the strip-form kernel addresses a row pair with 32-bit byte offsets
@@ -637,9 +633,7 @@ lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, fl
         // the next group's HBM-bound passes start when this group's are done, i.e. together with its apply pass
         HIP_TRY(ctx, hipEventRecord(ctx->ev_start[g + 1], stream));
         HIP_TRY(ctx, hipStreamWaitEvent(aux, ctx->ev_start[g + 1], 0));
-        Launch Sn = sub(g + 1);
-        Sn.ballast_lds = velo ? 0u : ctx->shadow_lds;
-        stats_passes(Sn, aux);
+        stats_passes(sub(g + 1), aux);
         HIP_TRY(ctx, hipEventRecord(ctx->ev_pre[g + 1], aux));
       }
       launch_apply(sub(g));

@@ -83,13 +83,11 @@ struct Launch {
   const ApplyTileDev* atiles;
   int n_atiles;
   int tensor0;   // first tensor of the sub-list this launch covers (the per-tensor kernels index from it)
-  unsigned ballast_lds;   // bytes of unused dynamic LDS requested by the streaming passes (bounds their workgroups per CU)
   int* apply_counter;     // tile counter of the strip-form apply kernel for this sub-list (cleared by k_finalize)
   int resident_wgs;       // workgroups of the strip-form apply kernel that are resident at once (2 per CU)
 };
 
 // kernels (lopt_kernels.hip / lopt_apply_mfma.hip)
-hipError_t enable_ballast_lds();
 void launch_fill_zero(const Launch&, const StepArgs&, hipStream_t);
 void launch_rowcol_sums(const Launch&, const StepArgs&, hipStream_t);
 void launch_rc_update(const Launch&, const StepArgs&, hipStream_t);

@@ -96,7 +96,7 @@ __global__ void __launch_bounds__(kBlock) k_rowcol_sums(const TensorDev* __restr
 
 void launch_rowcol_sums(const Launch& L, const StepArgs&, hipStream_t s) {
   if (L.n_tiles == 0) return;
-  hipLaunchKernelGGL(k_rowcol_sums, dim3(L.n_tiles), dim3(kBlock), L.ballast_lds, s, L.tensors, L.tiles, L.ws);
+  hipLaunchKernelGGL(k_rowcol_sums, dim3(L.n_tiles), dim3(kBlock), 0, s, L.tensors, L.tiles, L.ws);
 }
 
 // ----------------------------------------------------------------------------- rc_update
@@ -348,21 +348,12 @@ __global__ void __launch_bounds__(kBlock) k_accum_stats(const TensorDev* __restr
   block_sum<kNStat>(acc, red, ws + T.oStatPart + (size_t)lt * kStatStride);
 }
 
-// Called once per context: lets the two streaming kernels take up to the whole LDS as launch-time ballast.
-hipError_t enable_ballast_lds() {
-  hipError_t e = hipFuncSetAttribute((const void*)k_rowcol_sums, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute((const void*)k_accum_stats<true>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
-  if (e != hipSuccess) return e;
-  return hipFuncSetAttribute((const void*)k_accum_stats<false>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
-}
-
 void launch_accum_stats(const Launch& L, const StepArgs& A, hipStream_t s) {
   if (L.n_tiles == 0) return;
   if (A.eps_acc >= 1e-30f)
-    hipLaunchKernelGGL(k_accum_stats<true>, dim3(L.n_tiles), dim3(kBlock), L.ballast_lds, s, L.tensors, L.tiles, L.ws, A);
+    hipLaunchKernelGGL(k_accum_stats<true>, dim3(L.n_tiles), dim3(kBlock), 0, s, L.tensors, L.tiles, L.ws, A);
   else
-    hipLaunchKernelGGL(k_accum_stats<false>, dim3(L.n_tiles), dim3(kBlock), L.ballast_lds, s, L.tensors, L.tiles, L.ws, A);
+    hipLaunchKernelGGL(k_accum_stats<false>, dim3(L.n_tiles), dim3(kBlock), 0, s, L.tensors, L.tiles, L.ws, A);
 }
 
 // ----------------------------------------------------------------------------- finalize
