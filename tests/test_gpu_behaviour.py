@@ -69,6 +69,36 @@ def test_group_pipeline_is_bit_identical_to_one_stream(groups, monkeypatch):
 
 
 @pytest.mark.parametrize("kind", ["small_fc_lopt", "velo"])
+def test_per_pass_timing_changes_no_result_and_names_every_pass(kind, monkeypatch):
+    # With lopt_profile_enable the step runs pass after pass on one stream with events in between (no tensor groups);
+    # results must be bit-identical to the default launch plan, here forced to three groups.
+    import torch
+    import paper_2506_10315_amd as P
+    monkeypatch.setenv("LOPT_GROUPS", "3")
+    ref = _run(kind, 3)
+    cfg = Hn.make_cfg(kind) if kind == "small_fc_lopt" else Hn.make_cfg(kind, lstm_hidden=64, n_bank=32)
+    w = Hn.random_weights(cfg, 0)
+    specs = [W.TensorSpec(f"t{i}", s) for i, s in enumerate(SHAPES)]
+    case = Hn.Case(201, specs, "gauss_logscale")
+    opt = P.LearnedOptimizer(cfg, w, SHAPES, device="cuda:0")
+    opt.profile_enable(True)
+    p = [torch.from_numpy(case.p0(i)).to("cuda:0") for i in range(len(specs))]
+    for t in range(3):
+        g = [torch.from_numpy(case.grad(i, t)).to("cuda:0") for i in range(len(specs))]
+        opt.step(p, g, lr=0.7, weight_decay=0.01, step=t)
+    pass_ms, k = opt.profile_read()
+    torch.cuda.synchronize()
+    out = [x.cpu().numpy().copy() for x in p] + [x.cpu().numpy().copy() for x in opt.state]
+    opt.close()
+    assert k == 3 and set(pass_ms) == {"rowcol_sums", "rc_update", "accum_stats", "finalize", "velo_lstm", "velo_head", "apply"}
+    assert all(v >= 0.0 for v in pass_ms.values()) and pass_ms["apply"] > 0.0 and pass_ms["accum_stats"] > 0.0
+    if kind == "velo":
+        assert pass_ms["velo_lstm"] > 0.0 and pass_ms["velo_head"] > 0.0
+    for x, y in zip(ref, out):
+        assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
+
+
+@pytest.mark.parametrize("kind", ["small_fc_lopt", "velo"])
 def test_checkpoint_resume_is_bit_identical(kind):
     a = _run(kind, 6)
     b = _run(kind, 6, resume_at=3)
