@@ -56,13 +56,17 @@ __device__ __forceinline__ f16x8 pk8(unsigned a, unsigned b, unsigned c, unsigne
 
 // (a, b) -> packed hi pair and packed lo pair, hi = rtz_fp16(x), lo = rtz_fp16(x - hi). The residual
 // x - float(hi) is one mixed-precision FMA (v_fma_mix_f32 reads the fp16 half directly, full rate; the
-// variants that write an fp16 result run at half rate).
+// variants that write an fp16 result run at half rate). One assembly block for the four instructions: after a
+// separate asm statement the compiler has to assume an instruction whose result needs a wait state before its
+// next use and pads every split with an s_nop; none of these four needs one.
 __device__ __forceinline__ void split2(float a, float b, unsigned& hi, unsigned& lo) {
-  hi = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(a, b));
-  float ra, rb;
-  asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel_hi:[1,0,0]" : "=v"(ra) : "v"(hi), "v"(a));
-  asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(rb) : "v"(hi), "v"(b));
-  lo = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(ra, rb));
+  // the residuals overwrite the registers of a and b, the packed lo pair that of a
+  asm("v_cvt_pkrtz_f16_f32 %0, %1, %2\n\t"
+      "v_fma_mix_f32 %1, %0, -1.0, %1 op_sel_hi:[1,0,0]\n\t"
+      "v_fma_mix_f32 %2, %0, -1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]\n\t"
+      "v_cvt_pkrtz_f16_f32 %1, %1, %2"
+      : "=&v"(hi), "+v"(a), "+v"(b));
+  lo = __builtin_bit_cast(unsigned, a);
 }
 
 // one value -> (hi in bits 0..15, lo in bits 16..31)
@@ -80,6 +84,7 @@ struct StripLds {
   unsigned rowinj[kApplyRows + kRowSlack][32];  // [row of the tile][unit]: packed (hi, lo) of bias + row part
   float4 rowrs[kApplyRows + kRowSlack];         // rsqrt(r_k + eps) of the row, k = 0..2
   float w1row[6][32];                           // prepared first layer, rows of the row-constant features
+  float w1col[6][32];                           // prepared first layer, rows of the column-constant features
   float b1[32];                                 // prepared bias (time features folded in)
   float4 w3[2][8];                              // [half][v/2]: W3 rows d(v) m(v) d(v+1) m(v+1) of units unit_of(v, half)
 };
@@ -124,15 +129,14 @@ struct Consts {
 // operand of tile A (row q), registers 4..7 that of tile B (row q + 1).
 struct Feat { unsigned ph[8], pl[8]; float p_old; };
 
-struct FeatTmp { float rs, tg[3], tm[3]; };
+struct FeatTmp { float rs; };
 
-// The feature computation in six slices (one per MFMA of the phase it hides behind).
+// The feature computation in six slices (one per MFMA of the phase it hides behind). The products of the row and
+// column factors are formed in the slice that uses them (fewer values live across slices).
 template <int PIECE, bool RAW_RSQ>
 __device__ __forceinline__ void feat_piece(const Consts& C, const Elem& e, const float4& rr4, FeatTmp& t, Feat& f) {
   if (PIECE == 0) {
     t.rs = RAW_RSQ ? __builtin_amdgcn_rsqf(e.v + C.eps) : rsqrtf(e.v + C.eps);
-    t.tg[0] = rr4.x * C.fg[0]; t.tg[1] = rr4.y * C.fg[1]; t.tg[2] = rr4.z * C.fg[2];
-    t.tm[0] = rr4.x * C.fm[0]; t.tm[1] = rr4.y * C.fm[1]; t.tm[2] = rr4.z * C.fm[2];
     // an explicit copy: otherwise the old parameter value stays in the load's register, the next load of this
     // set lands elsewhere, and the loop's back edge needs a copy of a value that is still in flight
     asm volatile("v_mov_b32 %0, %1" : "=v"(f.p_old) : "v"(e.p));
@@ -144,10 +148,10 @@ __device__ __forceinline__ void feat_piece(const Consts& C, const Elem& e, const
     split2((e.m1 * t.rs) * C.sc[6], (e.m2 * t.rs) * C.sc[7], f.ph[3], f.pl[3]);
   } else if (PIECE == 3) {
     split2((e.m3 * t.rs) * C.sc[8], t.rs * C.sc[9], f.ph[4], f.pl[4]);
-    split2(e.g * t.tg[0], e.g * t.tg[1], f.ph[5], f.pl[5]);
+    split2(e.g * (rr4.x * C.fg[0]), e.g * (rr4.y * C.fg[1]), f.ph[5], f.pl[5]);
   } else if (PIECE == 4) {
-    split2(e.g * t.tg[2], e.m1 * t.tm[0], f.ph[6], f.pl[6]);
-    split2(e.m2 * t.tm[1], e.m3 * t.tm[2], f.ph[7], f.pl[7]);
+    split2(e.g * (rr4.z * C.fg[2]), e.m1 * (rr4.x * C.fm[0]), f.ph[6], f.pl[6]);
+    split2(e.m2 * (rr4.y * C.fm[1]), e.m3 * (rr4.z * C.fm[2]), f.ph[7], f.pl[7]);
   } else {
     swap32x8(f.ph, f.pl);
   }
@@ -237,9 +241,14 @@ __global__ void __launch_bounds__(kBlock, 2) k_apply_f16s(const TensorDev* __res
   const float* __restrict__ rst = T.st + 4 * (size_t)T.padN;   // r_k[3][padm] then c_k[3][padn]
   {
     const int t = threadIdx.x;
-    if (t < 192) L.w1row[t >> 5][t & 31] = prep[row_feat(t >> 5) * kH + (t & 31)];
-    else if (t < 224) L.b1[t - 192] = prep[kNF * kH + (t - 192)];
+    if (t < 192) {
+      L.w1row[t >> 5][t & 31] = prep[row_feat(t >> 5) * kH + (t & 31)];
+      L.w1col[t >> 5][t & 31] = prep[col_feat(t >> 5) * kH + (t & 31)];
+    } else if (t < 224) L.b1[t - 192] = prep[kNF * kH + (t - 192)];
   }
+#pragma unroll
+  for (int i = 0; i < 10; ++i) C.sc[i] = ws[T.oScale + i];
+  __syncthreads();   // w1row, w1col, b1
   // ---- column part of layer 1's C operand for this lane's column: units unit_of(v, half), v = 0..15
   {
     float cf[6];
@@ -255,15 +264,12 @@ __global__ void __launch_bounds__(kBlock, 2) k_apply_f16s(const TensorDev* __res
       float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
       for (int f = 0; f < 6; ++f) {
-        const float4 w = *reinterpret_cast<const float4*>(prep + col_feat(f) * kH + 8 * q + 4 * half);
+        const float4 w = *reinterpret_cast<const float4*>(&L.w1col[f][8 * q + 4 * half]);
         a.x += cf[f] * w.x; a.y += cf[f] * w.y; a.z += cf[f] * w.z; a.w += cf[f] * w.w;
       }
       C.colc[4 * q] = a.x; C.colc[4 * q + 1] = a.y; C.colc[4 * q + 2] = a.z; C.colc[4 * q + 3] = a.w;
     }
   }
-#pragma unroll
-  for (int i = 0; i < 10; ++i) C.sc[i] = ws[T.oScale + i];
-  __syncthreads();   // w1row, b1
   // ---- row part of the tile's rows -> LDS (thread: unit t & 31, rows (t >> 5), +8, ...); rows past the tile
   // hold zeros: the injection MFMA multiplies them by 0, and the pipeline's run-out rounds read them
   {
