@@ -41,7 +41,7 @@ ACCUM_BYTES = 40
 # scaled by the factors a plain 256 MiB copy gives (2.0 / 1.0): see profiles/hbm_traffic_vit_b16.md.
 # Keyed by (config, pass); other configurations report null.
 MEASURED_TRAFFIC_BYTES = {
-    (2, "apply"): (1_084_192 * 2.0 + 338_366) * 1024,
+    (2, "apply"): (1_044_777 * 2.0 + 338_455) * 1024,
     (2, "accum_stats"): (1_020_355 * 2.0 + 1_353_160) * 1024,
     (3, "apply"): (1_024_089 * 2.0 + 338_155) * 1024,
     (3, "accum_stats"): (1_020_277 * 2.0 + 1_353_160) * 1024,

@@ -303,8 +303,8 @@ __global__ void __launch_bounds__(kBlock, 2) k_apply_f16s(const TensorDev* __res
 
   // ---- streaming: lanes of the lower half read row q, lanes of the upper half row q + 1 (q - r0 even,
   // wave-uniform). Loads are unconditional: a column past the end reads the last column, the upper half of a
-  // tensor's last odd row reads the lower half's row, rows past the end read the last row; such lanes compute
-  // on real (finite) values and never store.
+  // tensor's last odd row reads the lower half's row, rounds past the tile read the tile's last row; such lanes
+  // compute on real (finite) values and never store.
   Streams S;
   S.g = (gcf32)T.g; S.p = (gcf32)T.p;
   S.m1 = (gcf32)T.st; S.m2 = S.m1 + T.padN; S.m3 = S.m2 + T.padN; S.v = S.m3 + T.padN;
@@ -312,9 +312,11 @@ __global__ void __launch_bounds__(kBlock, 2) k_apply_f16s(const TensorDev* __res
   // lane offsets in bytes (the host keeps tensors with 8 * cols >= 2^32 away from this kernel)
   const unsigned colc_ = 4u * (unsigned)(col_ok ? col : n - 1);
   const unsigned voff_pair = colc_ + (half ? 4u * (unsigned)n : 0u);
+  // the pipeline's run-out rounds (q >= r1) read the tile's last row once more: a cache hit, not HBM traffic
   auto fetch = [&](int q) __attribute__((always_inline)) {
-    const int qc = q < m ? q : m - 1;
-    return load_elem(S, (size_t)qc * (size_t)n, qc + 1 < m ? voff_pair : colc_);
+    const bool in_tile = q < r1;
+    const int qc = in_tile ? q : r1 - 1;
+    return load_elem(S, (size_t)qc * (size_t)n, in_tile && qc + 1 < m ? voff_pair : colc_);
   };
 
   // One step of the pipeline. On entry: h2a/h2b/p_e belong to the round of rows qe, qe+1 (layer 3 and update
