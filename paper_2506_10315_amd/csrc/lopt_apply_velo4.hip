@@ -31,7 +31,7 @@ __device__ __forceinline__ float relu1(float x) {
   return __builtin_bit_cast(float, i > 0 ? i : 0);
 }
 
-template <bool VEC>
+template <bool VEC, bool RAW_RSQ>
 __device__ __forceinline__ void apply_velo4_tile(const TensorDev& T, const TileDev& tile, const float* __restrict__ ws,
                                                  const StepArgs& A) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -120,7 +120,7 @@ __device__ __forceinline__ void apply_velo4_tile(const TensorDev& T, const TileD
     for (int e = 0; e < 4; ++e) {
       const float g = get(g4, e);
       const float q1 = get(m1, e), q2 = get(m2, e), q3 = get(m3, e), v = get(v4, e);
-      const float rs = rsqrtf(v + eps);
+      const float rs = RAW_RSQ ? __builtin_amdgcn_rsqf(v + eps) : rsqrtf(v + eps);
       const float f0 = rr[0] * get(rc[0], e), f1 = rr[1] * get(rc[1], e), f2 = rr[2] * get(rc[2], e);
       x[e][0] = g; x[e][1] = get(p4, e); x[e][2] = q1; x[e][3] = q2; x[e][4] = q3; x[e][5] = v;
       x[e][6] = q1 * rs; x[e][7] = q2 * rs; x[e][8] = q3 * rs; x[e][9] = rs;
@@ -154,7 +154,7 @@ __device__ __forceinline__ void apply_velo4_tile(const TensorDev& T, const TileD
     float pn[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const float delta = o[e][0] * expf(o[e][1] * A.exp_mult) * A.step_mult;
+      const float delta = o[e][0] * __expf(o[e][1] * A.exp_mult) * A.step_mult;
       const float p = get(p4, e);
       pn[e] = p - lr * (delta + wd * p);
     }
@@ -162,20 +162,26 @@ __device__ __forceinline__ void apply_velo4_tile(const TensorDev& T, const TileD
   }
 }
 
+template <bool RAW_RSQ>
 __global__ void __launch_bounds__(kBlock, 4) k_apply_velo4(const TensorDev* __restrict__ tensors,
                                                         const TileDev* __restrict__ tiles, float* __restrict__ ws,
                                                         StepArgs A) {
   const TileDev tile = tiles[blockIdx.x];
   const TensorDev& T = tensors[tile.tensor];
-  if (T.vec) apply_velo4_tile<true>(T, tile, ws, A);
-  else apply_velo4_tile<false>(T, tile, ws, A);
+  if (T.vec) apply_velo4_tile<true, RAW_RSQ>(T, tile, ws, A);
+  else apply_velo4_tile<false, RAW_RSQ>(T, tile, ws, A);
 }
 
 bool apply_velo4_available(const StepArgs& A) { return A.kind == LOPT_VELO && A.H == kVH && A.HP == kVH; }
 
 void launch_apply_velo4(const Launch& L, const StepArgs& A, hipStream_t s) {
   if (L.n_tiles == 0) return;
-  hipLaunchKernelGGL(k_apply_velo4, dim3(L.n_tiles), dim3(kBlock), 0, s, L.tensors, L.tiles, L.ws, A);
+  // v_rsq_f32 treats inputs below the smallest normal float as zero; with eps_acc that small the kernel takes the
+  // library reciprocal square root (which rescales such inputs) instead of the bare instruction
+  if (A.eps_acc >= 1e-30f)
+    hipLaunchKernelGGL(k_apply_velo4<true>, dim3(L.n_tiles), dim3(kBlock), 0, s, L.tensors, L.tiles, L.ws, A);
+  else
+    hipLaunchKernelGGL(k_apply_velo4<false>, dim3(L.n_tiles), dim3(kBlock), 0, s, L.tensors, L.tiles, L.ws, A);
 }
 
 }  // namespace lopt
