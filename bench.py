@@ -26,8 +26,9 @@ MFMA_F16_PEAK_TFLOPS = 2500.0     # dense fp16/bf16 matrix peak
 
 # Vector-ALU instruction issue: 256 CUs x 4 SIMDs, one wave64 instruction per 4 cycles and SIMD, 2.4 GHz
 VALU_ISSUE_PEAK_GINST = 256 * 4 * 2.4 / 4          # 614.4 G wave-instructions/s
-# k_apply_f16s executes 316 vector instructions (20 of them MFMAs) per round of 64 elements (profiles/sq_counters_vit_b16.md)
-APPLY_F16S_INST_PER_ROUND = 316
+# k_apply_f16s executes 320 vector instructions (20 of them MFMAs) per round of 64 elements, per-tile set-up and
+# pipeline fill included (profiles/sq_counters_vit_b16.md)
+APPLY_F16S_INST_PER_ROUND = 320
 
 # Algorithmic work per element of the dominant pass:
 #   apply pass, small_fc_lopt hidden 32: MLP contraction 28*32 + 32*32 + 32*2 MACs = 3968 FLOP
