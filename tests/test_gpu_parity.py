@@ -60,6 +60,34 @@ def test_tall_and_wide_tensors():
     Hn.run_free(Hn.Case(104, _specs([(9000, 256), (5504,), (4100, 8)]), "student_t3"), cfg, w, 3)
 
 
+def _random_shapes(seed, count):
+    """Seeded list of 1-D/2-D/3-D shapes with ragged sizes around the kernels' tile edges (4, 32, 64, 128, 256)."""
+    r = np.random.default_rng(seed)
+    edges = np.array([1, 2, 3, 4, 5, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 300, 513])
+    shapes = []
+    for _ in range(count):
+        kind = r.integers(0, 10)
+        a, b = int(r.choice(edges)), int(r.choice(edges))
+        if r.integers(0, 2):
+            a = int(r.integers(1, 400))
+        if kind == 0:
+            shapes.append((a,))
+        elif kind == 1:
+            shapes.append((int(r.integers(1, 4)), int(r.integers(1, 5)), b))
+        else:
+            shapes.append((a, b))
+    return shapes
+
+
+@pytest.mark.parametrize("kind,seed", [("small_fc_lopt", 11), ("small_fc_lopt", 12), ("velo", 13)])
+def test_random_shape_lists(kind, seed):
+    # shapes nobody picked by hand: every pass sees ragged first/last tiles in rows and columns
+    cfg = Hn.make_cfg(kind) if kind == "small_fc_lopt" else Hn.make_cfg(kind, lstm_hidden=32, n_bank=8)
+    w = Hn.random_weights(cfg, seed=seed)
+    Hn.run_free(Hn.Case(110 + seed, _specs(_random_shapes(seed, 24)), "gauss_logscale"), cfg, w, 3,
+                lr_fn=lambda t: 0.5, wd=0.01)
+
+
 @pytest.mark.parametrize("variant", ["valu", "mfma_f32", "mfma_f16x3", "mfma_f16s"])
 def test_every_apply_kernel_variant_matches_the_oracle(variant, monkeypatch):
     # LOPT_APPLY (read when the context is created) selects the apply kernel for hidden width 32:
