@@ -100,3 +100,14 @@ def test_workload_shapes_match_the_named_models():
     assert len(w5.tensors) == 219 + 2000
     assert sum(t.numel for t in w5.tensors[:219]) == 1_345_423_360
     assert all(1 <= t.numel <= 512 for t in w5.tensors[219:])
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # one GPU only: a request for more ends with a message before anything touches a device
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=300)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stdout + r.stderr)
