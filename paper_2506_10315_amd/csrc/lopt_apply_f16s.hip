@@ -460,7 +460,7 @@ __global__ void __launch_bounds__(kBlock, 2) k_apply_f16s(const TensorDev* __res
     es[0] = fetch(r0 + 2 * kSets);
     feat_piece<5, RAW_RSQ>(C, es[0], rr4, t, f);
   }
-  step(std::false_type{}, es[1 % kSets], r0 - 2);   // layers 1-2 of round 0, features of round 1
+  step(std::false_type{}, es[1 % kSets], r0 - 2);   // layers 1-2 of the first row pair, features of the second
   for (int q = r0; q < r1; q += 2 * kSets) {
 #pragma unroll
     for (int s = 0; s < kSets; ++s)   // update rows q + 2s, +1 (nothing is stored past the tile); features of round +2
