@@ -79,3 +79,68 @@ def test_config5_llama_1p3b_velo_full_size(capsys):
                           checks={0: big + tiny, 1: tiny[::10] + _idx(wl, ["layers.10.attn_norm"])},
                           progress=_progress(capsys))
     _progress(capsys)(f"config 5 worst: {worst}")
+
+
+@pytest.mark.parametrize("kind", ["small_fc_lopt", "velo"])
+def test_maximum_size_tensor_matches_its_periodic_base_pattern(kind, capsys):
+    """One tensor of 46340 x 46340 = 2,147,395,600 elements (the boundary admits up to 2^31 - 1 per tensor): byte
+    offsets beyond 2^32 in every streamed array. Parameters and gradients tile a 4 x 4 base pattern, so every row
+    mean, column mean and whole-tensor mean is that of the base pattern, and the oracle's result for the 4 x 4
+    tensor, tiled, is the expected value of EVERY element (all of them are compared, on the device). Two steps: the
+    second one runs on non-zero accumulators."""
+    import torch
+    import paper_2506_10315_amd as P
+    from oracle import lopt_oracle as O
+    say = _progress(capsys)
+    dev = "cuda:0"
+    reps, side = 11585, 46340
+    cfg = Hn.make_cfg(kind)
+    ocfg = Hn.oracle_config_from(cfg)
+    w = W.small_fc_weights(0, 32) if kind == "small_fc_lopt" else W.velo_weights(0)
+    rng = np.random.default_rng([20250610, 900, 0 if kind == "small_fc_lopt" else 1])
+    p_base = (rng.standard_normal((4, 4)) * 0.02).astype(np.float32)
+    g_base = [(rng.standard_normal((4, 4)) * 1e-3).astype(np.float32) for _ in range(2)]
+
+    def tile_into(dst2d, base):
+        dst2d.view(reps, 4, reps, 4).copy_(torch.from_numpy(base).to(dev).view(1, 4, 1, 4))
+
+    def tiled_err(t2d, base64):
+        # oracle.rel_err of the tiled expectation, evaluated on the device in row chunks
+        b = torch.from_numpy(np.asarray(base64, np.float64).astype(np.float32)).to(dev).view(1, 4, 1, 4)
+        rms = float(np.sqrt(np.mean(np.asarray(base64, np.float64) ** 2)))
+        den = b.abs() + rms
+        v = t2d.view(reps, 4, reps, 4)
+        worst = 0.0
+        for a0 in range(0, reps, 1024):
+            worst = max(worst, float(((v[a0:a0 + 1024] - b).abs_() / den).amax()))
+        return worst
+
+    def vec_err(t1d, base64):
+        exp = np.tile(np.asarray(base64, np.float64), reps)
+        return O.rel_err(t1d.cpu().numpy(), exp)
+
+    opt = P.LearnedOptimizer(cfg, w, [(side, side)], device=dev)
+    p = torch.empty((side, side), dtype=torch.float32, device=dev)
+    g = torch.empty((side, side), dtype=torch.float32, device=dev)
+    tile_into(p, p_base)
+    p_ora = p_base.astype(np.float64)
+    st = O.init_state(4, 4, ocfg)
+    lr, wd = 1.0, float(np.float32(0.01))
+    for t in range(2):
+        tile_into(g, g_base[t])
+        say(f"maximum size {kind}: step {t}")
+        opt.step([p], [g], lr=lr, weight_decay=wd, step=t)
+        torch.cuda.synchronize()
+        p_ora = O.tensor_step(p_ora, g_base[t], st, w, ocfg, t, lr, wd, ndim=2)
+        e = tiled_err(p, p_ora)
+        assert e <= Hn.TOL_PARAM, f"step {t}: parameter rel err {e:.3e}"
+        sv = opt.state_views(0)
+        for k in range(3):
+            assert tiled_err(sv["M"][k], st["M"][k]) <= Hn.TOL_ACC, f"step {t}: M{k + 1}"
+            assert vec_err(sv["r"][k], st["r"][k]) <= Hn.TOL_ACC, f"step {t}: r{k + 1}"
+            assert vec_err(sv["c"][k], st["c"][k]) <= Hn.TOL_ACC, f"step {t}: c{k + 1}"
+        assert tiled_err(sv["V"], st["V"]) <= Hn.TOL_ACC, f"step {t}: V"
+        say(f"maximum size {kind}: step {t} parameter rel err {e:.2e}")
+    opt.close()
+    del p, g
+    torch.cuda.empty_cache()
