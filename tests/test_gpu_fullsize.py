@@ -81,19 +81,16 @@ def test_config5_llama_1p3b_velo_full_size(capsys):
     _progress(capsys)(f"config 5 worst: {worst}")
 
 
-@pytest.mark.parametrize("kind", ["small_fc_lopt", "velo"])
-def test_maximum_size_tensor_matches_its_periodic_base_pattern(kind, capsys):
-    """One tensor of 46340 x 46340 = 2,147,395,600 elements (the boundary admits up to 2^31 - 1 per tensor): byte
-    offsets beyond 2^32 in every streamed array. Parameters and gradients tile a 4 x 4 base pattern, so every row
-    mean, column mean and whole-tensor mean is that of the base pattern, and the oracle's result for the 4 x 4
+def _periodic_tensor_case(kind, reps_r, reps_c, say, tag):
+    """One tensor of (4 reps_r) x (4 reps_c) elements whose parameters and gradients tile a 4 x 4 base pattern: every
+    row mean, column mean and whole-tensor mean is that of the base pattern, so the oracle's result for the 4 x 4
     tensor, tiled, is the expected value of EVERY element (all of them are compared, on the device). Two steps: the
     second one runs on non-zero accumulators."""
     import torch
     import paper_2506_10315_amd as P
     from oracle import lopt_oracle as O
-    say = _progress(capsys)
     dev = "cuda:0"
-    reps, side = 11585, 46340
+    rows, cols = 4 * reps_r, 4 * reps_c
     cfg = Hn.make_cfg(kind)
     ocfg = Hn.oracle_config_from(cfg)
     w = W.small_fc_weights(0, 32) if kind == "small_fc_lopt" else W.velo_weights(0)
@@ -102,33 +99,40 @@ def test_maximum_size_tensor_matches_its_periodic_base_pattern(kind, capsys):
     g_base = [(rng.standard_normal((4, 4)) * 1e-3).astype(np.float32) for _ in range(2)]
 
     def tile_into(dst2d, base):
-        dst2d.view(reps, 4, reps, 4).copy_(torch.from_numpy(base).to(dev).view(1, 4, 1, 4))
+        dst2d.view(reps_r, 4, reps_c, 4).copy_(torch.from_numpy(base).to(dev).view(1, 4, 1, 4))
 
     def tiled_err(t2d, base64):
-        # oracle.rel_err of the tiled expectation, evaluated on the device in row chunks
+        # oracle.rel_err of the tiled expectation, evaluated on the device in chunks of about 2^28 elements
         b = torch.from_numpy(np.asarray(base64, np.float64).astype(np.float32)).to(dev).view(1, 4, 1, 4)
         rms = float(np.sqrt(np.mean(np.asarray(base64, np.float64) ** 2)))
         den = b.abs() + rms
-        v = t2d.view(reps, 4, reps, 4)
+        v = t2d.view(reps_r, 4, reps_c, 4)
         worst = 0.0
-        for a0 in range(0, reps, 1024):
-            worst = max(worst, float(((v[a0:a0 + 1024] - b).abs_() / den).amax()))
+        if reps_r > 1:
+            step = max(1, (1 << 24) // reps_c)
+            for a0 in range(0, reps_r, step):
+                worst = max(worst, float(((v[a0:a0 + step] - b).abs_() / den).amax()))
+        else:
+            for c0 in range(0, reps_c, 1 << 24):
+                worst = max(worst, float(((v[:, :, c0:c0 + (1 << 24)] - b).abs_() / den).amax()))
         return worst
 
-    def vec_err(t1d, base64):
-        exp = np.tile(np.asarray(base64, np.float64), reps)
-        return O.rel_err(t1d.cpu().numpy(), exp)
+    def vec_err(t1d, base64, reps):
+        # a vector over rows or columns: compared on the device against the tiled 4 values
+        b = torch.from_numpy(np.asarray(base64, np.float64).astype(np.float32)).to(dev).view(1, 4)
+        rms = float(np.sqrt(np.mean(np.asarray(base64, np.float64) ** 2)))
+        return float(((t1d.view(reps, 4) - b).abs() / (b.abs() + rms)).amax())
 
-    opt = P.LearnedOptimizer(cfg, w, [(side, side)], device=dev)
-    p = torch.empty((side, side), dtype=torch.float32, device=dev)
-    g = torch.empty((side, side), dtype=torch.float32, device=dev)
+    opt = P.LearnedOptimizer(cfg, w, [(rows, cols)], device=dev)
+    p = torch.empty((rows, cols), dtype=torch.float32, device=dev)
+    g = torch.empty((rows, cols), dtype=torch.float32, device=dev)
     tile_into(p, p_base)
     p_ora = p_base.astype(np.float64)
     st = O.init_state(4, 4, ocfg)
     lr, wd = 1.0, float(np.float32(0.01))
     for t in range(2):
         tile_into(g, g_base[t])
-        say(f"maximum size {kind}: step {t}")
+        say(f"{tag} {kind}: step {t}")
         opt.step([p], [g], lr=lr, weight_decay=wd, step=t)
         torch.cuda.synchronize()
         p_ora = O.tensor_step(p_ora, g_base[t], st, w, ocfg, t, lr, wd, ndim=2)
@@ -137,10 +141,23 @@ def test_maximum_size_tensor_matches_its_periodic_base_pattern(kind, capsys):
         sv = opt.state_views(0)
         for k in range(3):
             assert tiled_err(sv["M"][k], st["M"][k]) <= Hn.TOL_ACC, f"step {t}: M{k + 1}"
-            assert vec_err(sv["r"][k], st["r"][k]) <= Hn.TOL_ACC, f"step {t}: r{k + 1}"
-            assert vec_err(sv["c"][k], st["c"][k]) <= Hn.TOL_ACC, f"step {t}: c{k + 1}"
+            assert vec_err(sv["r"][k], st["r"][k], reps_r) <= Hn.TOL_ACC, f"step {t}: r{k + 1}"
+            assert vec_err(sv["c"][k], st["c"][k], reps_c) <= Hn.TOL_ACC, f"step {t}: c{k + 1}"
         assert tiled_err(sv["V"], st["V"]) <= Hn.TOL_ACC, f"step {t}: V"
-        say(f"maximum size {kind}: step {t} parameter rel err {e:.2e}")
+        say(f"{tag} {kind}: step {t} parameter rel err {e:.2e}")
     opt.close()
     del p, g
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("kind", ["small_fc_lopt", "velo"])
+def test_maximum_size_tensor_matches_its_periodic_base_pattern(kind, capsys):
+    # 46340 x 46340 = 2,147,395,600 elements (the boundary admits up to 2^31 - 1 per tensor): byte offsets beyond 2^32
+    # in every streamed array
+    _periodic_tensor_case(kind, 11585, 11585, _progress(capsys), "maximum size")
+
+
+def test_widest_tensor_matches_its_periodic_base_pattern(capsys):
+    # 4 x 2^28: a million column tiles per pass, and the width from which the strip-form apply kernel (32-bit byte
+    # offsets inside a row pair) hands the list to the row-form kernel
+    _periodic_tensor_case("small_fc_lopt", 1, 1 << 26, _progress(capsys), "widest")
