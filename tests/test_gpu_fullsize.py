@@ -161,3 +161,9 @@ def test_widest_tensor_matches_its_periodic_base_pattern(capsys):
     # 4 x 2^28: a million column tiles per pass, and the width from which the strip-form apply kernel (32-bit byte
     # offsets inside a row pair) hands the list to the row-form kernel
     _periodic_tensor_case("small_fc_lopt", 1, 1 << 26, _progress(capsys), "widest")
+
+
+def test_tallest_tensor_matches_its_periodic_base_pattern(capsys):
+    # 2^28 x 4: the tallest statistics tiles (64 row tiles of 4,194,304 rows), a million row blocks in the row/column
+    # pass, apply tiles with one of four column strips in use
+    _periodic_tensor_case("small_fc_lopt", 1 << 26, 1, _progress(capsys), "tallest")
