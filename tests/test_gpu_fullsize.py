@@ -81,32 +81,32 @@ def test_config5_llama_1p3b_velo_full_size(capsys):
     _progress(capsys)(f"config 5 worst: {worst}")
 
 
-def _periodic_tensor_case(kind, reps_r, reps_c, say, tag):
-    """One tensor of (4 reps_r) x (4 reps_c) elements whose parameters and gradients tile a 4 x 4 base pattern: every
-    row mean, column mean and whole-tensor mean is that of the base pattern, so the oracle's result for the 4 x 4
+def _periodic_tensor_case(kind, reps_r, reps_c, say, tag, pr=4, pc=4):
+    """One tensor of (pr reps_r) x (pc reps_c) elements whose parameters and gradients tile a pr x pc base pattern: every
+    row mean, column mean and whole-tensor mean is that of the base pattern, so the oracle's result for the pr x pc
     tensor, tiled, is the expected value of EVERY element (all of them are compared, on the device). Two steps: the
     second one runs on non-zero accumulators."""
     import torch
     import paper_2506_10315_amd as P
     from oracle import lopt_oracle as O
     dev = "cuda:0"
-    rows, cols = 4 * reps_r, 4 * reps_c
+    rows, cols = pr * reps_r, pc * reps_c
     cfg = Hn.make_cfg(kind)
     ocfg = Hn.oracle_config_from(cfg)
     w = W.small_fc_weights(0, 32) if kind == "small_fc_lopt" else W.velo_weights(0)
     rng = np.random.default_rng([20250610, 900, 0 if kind == "small_fc_lopt" else 1])
-    p_base = (rng.standard_normal((4, 4)) * 0.02).astype(np.float32)
-    g_base = [(rng.standard_normal((4, 4)) * 1e-3).astype(np.float32) for _ in range(2)]
+    p_base = (rng.standard_normal((pr, pc)) * 0.02).astype(np.float32)
+    g_base = [(rng.standard_normal((pr, pc)) * 1e-3).astype(np.float32) for _ in range(2)]
 
     def tile_into(dst2d, base):
-        dst2d.view(reps_r, 4, reps_c, 4).copy_(torch.from_numpy(base).to(dev).view(1, 4, 1, 4))
+        dst2d.view(reps_r, pr, reps_c, pc).copy_(torch.from_numpy(base).to(dev).view(1, pr, 1, pc))
 
     def tiled_err(t2d, base64):
         # oracle.rel_err of the tiled expectation, evaluated on the device in chunks of about 2^28 elements
-        b = torch.from_numpy(np.asarray(base64, np.float64).astype(np.float32)).to(dev).view(1, 4, 1, 4)
+        b = torch.from_numpy(np.asarray(base64, np.float64).astype(np.float32)).to(dev).view(1, pr, 1, pc)
         rms = float(np.sqrt(np.mean(np.asarray(base64, np.float64) ** 2)))
         den = b.abs() + rms
-        v = t2d.view(reps_r, 4, reps_c, 4)
+        v = t2d.view(reps_r, pr, reps_c, pc)
         worst = 0.0
         if reps_r > 1:
             step = max(1, (1 << 24) // reps_c)
@@ -118,17 +118,18 @@ def _periodic_tensor_case(kind, reps_r, reps_c, say, tag):
         return worst
 
     def vec_err(t1d, base64, reps):
-        # a vector over rows or columns: compared on the device against the tiled 4 values
-        b = torch.from_numpy(np.asarray(base64, np.float64).astype(np.float32)).to(dev).view(1, 4)
+        # a vector over rows or columns: compared on the device against the tiled base values
+        k = len(base64)
+        b = torch.from_numpy(np.asarray(base64, np.float64).astype(np.float32)).to(dev).view(1, k)
         rms = float(np.sqrt(np.mean(np.asarray(base64, np.float64) ** 2)))
-        return float(((t1d.view(reps, 4) - b).abs() / (b.abs() + rms)).amax())
+        return float(((t1d.view(reps, k) - b).abs() / (b.abs() + rms)).amax())
 
     opt = P.LearnedOptimizer(cfg, w, [(rows, cols)], device=dev)
     p = torch.empty((rows, cols), dtype=torch.float32, device=dev)
     g = torch.empty((rows, cols), dtype=torch.float32, device=dev)
     tile_into(p, p_base)
     p_ora = p_base.astype(np.float64)
-    st = O.init_state(4, 4, ocfg)
+    st = O.init_state(pr, pc, ocfg)
     lr, wd = 1.0, float(np.float32(0.01))
     for t in range(2):
         tile_into(g, g_base[t])
@@ -167,3 +168,10 @@ def test_tallest_tensor_matches_its_periodic_base_pattern(capsys):
     # 2^28 x 4: the tallest statistics tiles (64 row tiles of 4,194,304 rows), a million row blocks in the row/column
     # pass, apply tiles with one of four column strips in use
     _periodic_tensor_case("small_fc_lopt", 1 << 26, 1, _progress(capsys), "tallest")
+
+
+@pytest.mark.parametrize("kind", ["small_fc_lopt", "velo"])
+def test_maximum_size_tensor_with_unaligned_rows(kind, capsys):
+    # 32768 x 65535 = 2,147,450,880 elements, rows of 65535 floats (not a multiple of 4): the scalar-access
+    # instantiations of every pass at byte offsets beyond 2^32; base pattern 4 x 3
+    _periodic_tensor_case(kind, 8192, 21845, _progress(capsys), "maximum size, unaligned rows", pr=4, pc=3)
