@@ -13,7 +13,7 @@
  *    workspace are DEVICE memory owned by the caller (fp32, 16-byte aligned).
  *  - The library owns only the lopt_ctx: a device copy of the optimizer's weights,
  *    a cached device table describing the tensor list, a pinned staging buffer and
- *    (small_fc_lopt) one extra stream with its events.
+ *    one extra stream with its events.
  *    lopt_step allocates device memory only when the tensor list changes.
  *  - All device work is ordered by the HIP stream passed in (a hipStream_t cast to
  *    void*, NULL = default stream): it starts after everything enqueued on that
@@ -28,6 +28,10 @@
  *    returns a status; nothing throws or aborts across this boundary. After a
  *    non-OK status, params and state are untouched and lopt_last_error() gives a
  *    message.
+ *  - A context is not thread-safe: calls on one context must not overlap on the host, and
+ *    steps enqueued through one context on different streams are not ordered with respect to
+ *    each other by the library (they share the context's tables and the caller's workspace).
+ *    Use one context per concurrently running optimizer.
  *  - Results are deterministic: the same inputs give bit-identical outputs (all
  *    reductions have a fixed order; no floating-point atomics).
  *  - A tensor is described as a row-major rows x cols matrix. The caller flattens:
