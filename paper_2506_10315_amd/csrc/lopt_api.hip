@@ -209,8 +209,10 @@ void build_plan(const lopt_ctx* ctx, size_t n, const lopt_tensor_desc* d, Plan* 
     const int units = (m + kRowUnit - 1) / kRowUnit;
     const int q = (units + kMaxRowTiles - 1) / kMaxRowTiles;
     T.TR = kRowUnit * (q < 1 ? 1 : q) / shrink;   // a multiple of 8: every wavefront of a tile owns whole rows
-    // ... but never more than kMaxRowTiles row tiles per tensor (the second-stage reductions loop over them) ...
-    const int min_tr = ((m + kMaxRowTiles - 1) / kMaxRowTiles + 7) & ~7;
+    // ... but never more than kMaxRowTiles row tiles per tensor (the second-stage reductions loop over them; a small
+    // list, whose tiles were made shorter above, may have `shrink` times as many) ...
+    const int max_rt = kMaxRowTiles * shrink;
+    const int min_tr = ((m + max_rt - 1) / max_rt + 7) & ~7;
     if (T.TR < min_tr) T.TR = min_tr;
     // ... unless that makes a tile taller than kMaxTileRows: a lane sums a quarter of the tile's rows in fp32
     // (four values per row), and such a partial sum must stay at about a thousand terms. Tensors of more than

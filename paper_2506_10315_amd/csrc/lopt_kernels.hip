@@ -117,6 +117,23 @@ __device__ __forceinline__ void block_sum(float (&v)[NV], float (*red)[4], float
   }
 }
 
+// Sum of part[0], part[stride], ... (count terms) in double, always in index order. The loads of a batch issue
+// ahead of the adds: batches of 32 while that many terms are left (the loop is bound by load latency), then 8.
+__device__ __forceinline__ double strided_sum(const float* __restrict__ part, int count, size_t stride) {
+  double acc = 0.0;
+  int j = 0;
+  for (; j + 32 <= count; j += 32) {
+    float t[32];
+#pragma unroll
+    for (int k = 0; k < 32; ++k) t[k] = part[(size_t)(j + k) * stride];
+#pragma unroll
+    for (int k = 0; k < 32; ++k) acc += (double)t[k];
+  }
+#pragma unroll 8
+  for (; j < count; ++j) acc += (double)part[(size_t)j * stride];
+  return acc;
+}
+
 __global__ void __launch_bounds__(kBlock) k_rc_update(const TensorDev* __restrict__ tensors,
                                                       const RcItemDev* __restrict__ items, float* __restrict__ ws,
                                                       StepArgs A) {
@@ -130,10 +147,7 @@ __global__ void __launch_bounds__(kBlock) k_rc_update(const TensorDev* __restric
   float* st = T.st;
   if (!it.is_col) {
     if (idx < T.m) {
-      const float* part = ws + T.oRowPart + idx;
-      double acc = 0.0;
-#pragma unroll 8
-      for (int j = 0; j < T.nct; ++j) acc += (double)part[(size_t)j * T.m];   // loads issue ahead, adds stay in order
+      const double acc = strided_sum(ws + T.oRowPart + idx, T.nct, (size_t)T.m);
       const float R = (float)(acc / (double)T.n);
 #pragma unroll
       for (int k = 0; k < 3; ++k) {
@@ -150,10 +164,7 @@ __global__ void __launch_bounds__(kBlock) k_rc_update(const TensorDev* __restric
     }
   } else {
     if (idx < T.n) {
-      const float* part = ws + T.oColPart + idx;
-      double acc = 0.0;
-#pragma unroll 8
-      for (int i = 0; i < T.nrt; ++i) acc += (double)part[(size_t)i * T.n];
+      const double acc = strided_sum(ws + T.oColPart + idx, T.nrt, (size_t)T.n);
       const float C = (float)(acc / (double)T.m);
 #pragma unroll
       for (int k = 0; k < 3; ++k) {
@@ -378,11 +389,8 @@ __global__ void __launch_bounds__(kBlock) k_finalize(const TensorDev* __restrict
   const int ntiles = T.nrt * T.nct;
   // per-element statistics: 17 sums over the tiles
   double a = 0.0;
-  if (q < kNStat) {
-    const float* sp = ws + T.oStatPart + q;
-#pragma unroll 8
-    for (int i = seg; i < ntiles; i += 8) a += (double)sp[(size_t)i * kStatStride];
-  }
+  if (q < kNStat && seg < ntiles)   // thread (seg, q): tiles seg, seg + 8, ...
+    a = strided_sum(ws + T.oStatPart + q + (size_t)seg * kStatStride, (ntiles - seg + 7) / 8, (size_t)8 * kStatStride);
   part[seg][q] = a;
   __syncthreads();
   if (threadIdx.x < 32) {
