@@ -193,6 +193,11 @@ def main():
         roofline["valu_issue"] = {"achieved": ginst, "peak": VALU_ISSUE_PEAK_GINST, "unit": "G wave-instructions/s",
                                   "frac": ginst / VALU_ISSUE_PEAK_GINST,
                                   "note": "executed vector instructions per 64 elements x rounds / launch time"}
+    if bound == "mfma":
+        # the same algorithmic FLOP rate against the fp32 vector-ALU peak (what a kernel without matrix cores could reach)
+        roofline["frac_of_fp32_vector_peak"] = achieved / MFMA_F32_PEAK_TFLOPS
+    # whole step against the HBM roof at 72 algorithmic bytes per element (three sweeps: 4 + 40 + 28)
+    roofline["step_hbm_frac"] = (72.0 * n_el / (dt / args.steps) / 1e9) / HBM_PEAK_GBS
     roofline["timing_note"] = ("pass_ms / avg_launch_ms: second run of the same K steps with per-pass HIP events, every pass "
                                "over the whole list on one stream (the tensor-group pipeline is off while events are on)")
     # every HBM-bound pass against the 8 TB/s roof (algorithmic bytes per element: 4 / 40 / 28)
