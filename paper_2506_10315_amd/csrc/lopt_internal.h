@@ -13,7 +13,7 @@ constexpr int kBlock = 256;       // threads per workgroup (4 wavefronts of 64)
 constexpr int kWave = 64;
 constexpr int kTileCols = 256;    // one wavefront row-segment: 64 lanes x float4
 constexpr int kRowUnit = 64;      // standard tile height (taller for tall tensors, shorter for small lists)
-constexpr int kMaxRowTiles = 64;  // tile height grows so that a large tensor has at most this many row tiles ...
+constexpr int kMaxRowTiles = 256; // tile height grows so that a large tensor has at most this many row tiles ...
 constexpr int kMaxTileRows = 1024; // ... up to this height (bounds the length of the per-lane fp32 partial sums)
 constexpr int kStatStride = 20;   // floats per tile in the per-tile statistics partials (17 used)
 constexpr int kRcStride = 12;     // floats per block in the row/column partials (9 used)

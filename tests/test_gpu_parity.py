@@ -54,10 +54,10 @@ def test_velo_config1_shapes_free_running_with_clip_active():
 
 
 def test_tall_and_wide_tensors():
-    # tall: more than 64 row tiles' worth of rows (tile height grows); wide 1-D: many column tiles
+    # tall: more rows than 256 standard row tiles hold (the tile height grows); wide 1-D: many column tiles
     cfg = Hn.make_cfg("small_fc_lopt")
     w = W.small_fc_weights(1, 32)
-    Hn.run_free(Hn.Case(104, _specs([(9000, 256), (5504,), (4100, 8)]), "student_t3"), cfg, w, 3)
+    Hn.run_free(Hn.Case(104, _specs([(9000, 256), (5504,), (4100, 8), (40000, 4)]), "student_t3"), cfg, w, 3)
 
 
 def _random_shapes(seed, count):
