@@ -218,3 +218,51 @@ def run_forced(case: Case, cfg, weights, steps, checks, lr_fn=lambda t: 1.0, wd=
         assert bool(torch.isfinite(p_gpu[i]).all()), f"tensor {i}: non-finite parameter at the end"
     opt.close()
     return worst
+
+
+def run_free_subset(case: Case, cfg, weights, steps, subset, check_steps, lr_fn=lambda t: 1.0, wd=0.0,
+                    device="cuda:0", progress=print):
+    """Free-running parity over many steps at full size. The GPU takes `steps` steps over ALL tensors of the case
+    (one lopt_step per step); the oracle free-runs the tensors in `subset` from the same start (every tensor's step
+    depends on that tensor alone) and parameters and accumulators are compared after the steps in `check_steps`.
+    Tensors outside the subset get seeded on-device parameters and gradients."""
+    import torch
+    import paper_2506_10315_amd as P
+    ocfg = oracle_config_from(cfg)
+    n = len(case.specs)
+    sub = sorted(subset)
+    opt = P.LearnedOptimizer(cfg, weights, [s.shape for s in case.specs], device=device)
+    p_gpu = []
+    for i in range(n):
+        if i in sub:
+            p_gpu.append(torch.from_numpy(case.p0(i)).to(device))
+        else:
+            gen = torch.Generator(device=device)
+            gen.manual_seed(W.BASE_SEED + 7919 * case.indices[i])
+            _, rows, cols = case.specs[i].as_2d()
+            p_gpu.append(torch.randn(rows, cols, generator=gen, device=device, dtype=torch.float32) * 0.02)
+    p_ora = {i: case.p0(i).astype(np.float64) for i in sub}
+    st_ora = {i: O.init_state(*p_ora[i].shape, ocfg) for i in sub}
+    worst = {"param": 0.0, "acc": 0.0}
+    for t in range(steps):
+        gs = {i: case.grad(i, t) for i in sub}
+        g_gpu = [torch.from_numpy(gs[i]).to(device) if i in gs else _device_grad(case, i, t, device) for i in range(n)]
+        lr, wdf = float(np.float32(lr_fn(t))), float(np.float32(wd))
+        opt.step(p_gpu, g_gpu, lr=lr, weight_decay=wdf, step=t)
+        for i in sub:
+            p_ora[i] = O.tensor_step(p_ora[i], gs[i], st_ora[i], weights, ocfg, t, lr, wdf, ndim=case.specs[i].as_2d()[0])
+        if t in check_steps:
+            torch.cuda.synchronize()
+            for i in sub:
+                tag = f"step {t} tensor {i} {case.specs[i].name} {case.specs[i].shape}"
+                e = O.rel_err(p_gpu[i].cpu().numpy(), p_ora[i])
+                worst["param"] = max(worst["param"], e)
+                assert e <= TOL_PARAM, f"{tag}: parameter rel err {e:.3e}"
+                worst["acc"] = max(worst["acc"], compare_state(gpu_state_to_numpy(opt, i), st_ora[i], tag))
+            progress(f"  step {t}: worst so far {worst}")
+        del g_gpu
+    torch.cuda.synchronize()
+    for i in range(n):
+        assert bool(torch.isfinite(p_gpu[i]).all()), f"tensor {i}: non-finite parameter at the end"
+    opt.close()
+    return worst

@@ -175,3 +175,45 @@ def test_maximum_size_tensor_with_unaligned_rows(kind, capsys):
     # 32768 x 65535 = 2,147,450,880 elements, rows of 65535 floats (not a multiple of 4): the scalar-access
     # instantiations of every pass at byte offsets beyond 2^32; base pattern 4 x 3
     _periodic_tensor_case(kind, 8192, 21845, _progress(capsys), "maximum size, unaligned rows", pr=4, pc=3)
+
+
+VIT_LONG_RUN = ["cls_token", "pos_embed", "patch_embed.bias", "blocks.5.norm1.weight", "blocks.5.attn.qkv.bias",
+                "blocks.11.mlp.fc1.bias", "blocks.0.mlp.fc2.bias", "norm.bias", "head.bias"]
+
+
+@pytest.mark.parametrize("config", [2, 3])
+def test_vit_b16_hundred_steps_free_running(config, capsys):
+    # the configurations' own step count (100), learning-rate schedule and weight decay: the GPU steps the whole
+    # ViT-B/16 set, the oracle free-runs nine of its tensors (one 2-D, 160 k elements in all) beside it
+    wl = W.get_workload(config)
+    cfg = Hn.make_cfg(wl.optimizer)
+    w = W.small_fc_weights(0, 32) if wl.optimizer == "small_fc_lopt" else W.velo_weights(0)
+    worst = Hn.run_free_subset(Hn.Case(config, wl.tensors, wl.grad_kind), cfg, w, wl.steps, _idx(wl, VIT_LONG_RUN),
+                               check_steps={0, 9, 24, 49, 74, wl.steps - 1}, lr_fn=lambda t: W.lr_at(wl, t),
+                               wd=wl.weight_decay, progress=_progress(capsys))
+    _progress(capsys)(f"config {config}, {wl.steps} steps free-running: worst {worst}")
+
+
+@pytest.mark.parametrize("optimizer", ["small_fc_lopt", "velo"])
+def test_gpt2_medium_fifty_steps_free_running(optimizer, capsys):
+    # configuration 4 at its own step count (50, Student-t gradients); the oracle free-runs eight of the 1-D tensors
+    # (the smallest 2-D tensor of this set has a million elements: the two-dimensional long run is the ViT-B/16 one)
+    wl = W.get_workload(4, optimizer)
+    cfg = Hn.make_cfg(optimizer)
+    w = W.small_fc_weights(0, 32) if optimizer == "small_fc_lopt" else W.velo_weights(0)
+    names = ["h.0.ln_1.weight", "h.3.attn.q.bias", "h.7.mlp.fc.bias", "h.12.ln_2.bias", "h.20.mlp.proj.bias",
+             "h.23.attn.proj.bias", "ln_f.weight", "ln_f.bias"]
+    worst = Hn.run_free_subset(Hn.Case(4, wl.tensors, wl.grad_kind), cfg, w, wl.steps, _idx(wl, names),
+                               check_steps={0, 9, 24, wl.steps - 1}, progress=_progress(capsys))
+    _progress(capsys)(f"config 4 {optimizer}, {wl.steps} steps free-running: worst {worst}")
+
+
+def test_llama_1p3b_twenty_steps_free_running(capsys):
+    # configuration 5 at its own step count (20): the oracle free-runs 100 of the 2000 tiny tensors and three norm vectors
+    wl = W.get_workload(5)
+    cfg = Hn.make_cfg("velo")
+    tiny = [i for i, t in enumerate(wl.tensors) if t.name.startswith("tiny.")]
+    sub = tiny[::20] + _idx(wl, ["layers.0.attn_norm", "layers.10.attn_norm", "norm"])
+    worst = Hn.run_free_subset(Hn.Case(5, wl.tensors, wl.grad_kind), cfg, W.velo_weights(0), wl.steps, sub,
+                               check_steps={0, 4, 9, wl.steps - 1}, progress=_progress(capsys))
+    _progress(capsys)(f"config 5, {wl.steps} steps free-running: worst {worst}")
