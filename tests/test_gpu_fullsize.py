@@ -3,7 +3,10 @@ times (every tensor of the model in one lopt_step). The oracle verifies sampled 
 element (one tensor of every shape class; the oracle needs ~2.6 s per million elements), every tensor is
 checked against the closed forms that hold after the first step, and all outputs must stay finite.
 Tensors too large for the oracle in a test (the 51M / 65M-element embeddings) are covered by the closed
-forms here and by tests/test_gpu_parity.py::test_tall_and_wide_tensors for the tall-tile code path."""
+forms here and by tests/test_gpu_parity.py::test_tall_and_wide_tensors for the tall-tile code path.
+Further down: tensors at the size limits (inputs that tile a small pattern, so that the oracle's result for the
+pattern is the expected value of every element), and free-running runs over each configuration's own step count
+with the oracle stepping a subset of the tensors beside the GPU."""
 import numpy as np
 import pytest
 
