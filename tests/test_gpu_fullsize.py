@@ -220,3 +220,40 @@ def test_llama_1p3b_twenty_steps_free_running(capsys):
     worst = Hn.run_free_subset(Hn.Case(5, wl.tensors, wl.grad_kind), cfg, W.velo_weights(0), wl.steps, sub,
                                check_steps={0, 4, 9, wl.steps - 1}, progress=_progress(capsys))
     _progress(capsys)(f"config 5, {wl.steps} steps free-running: worst {worst}")
+
+
+def test_config2_default_launch_plan_is_bit_identical_to_one_stream_at_full_size(monkeypatch):
+    # ViT-B/16 shapes: the default plan (four tensor groups on two streams, tiles from a device counter) against every
+    # pass over the whole list on one stream; three steps on seeded on-device inputs; parameters and state compared
+    # bit by bit on the device
+    import torch
+    import paper_2506_10315_amd as P
+    wl = W.get_workload(2)
+    cfg = Hn.make_cfg("small_fc_lopt")
+    w = W.small_fc_weights(0, 32)
+    case = Hn.Case(2, wl.tensors, wl.grad_kind)
+    dev = "cuda:0"
+
+    def run():
+        opt = P.LearnedOptimizer(cfg, w, [t.shape for t in wl.tensors], device=dev)
+        ps = []
+        for i, t in enumerate(wl.tensors):
+            gen = torch.Generator(device=dev)
+            gen.manual_seed(W.BASE_SEED + 7919 * i)
+            _, rows, cols = t.as_2d()
+            ps.append(torch.randn(rows, cols, generator=gen, device=dev, dtype=torch.float32) * 0.02)
+        for s in range(3):
+            gs = [Hn._device_grad(case, i, s, dev) for i in range(len(wl.tensors))]
+            opt.step(ps, gs, lr=0.5, weight_decay=0.01, step=s)
+        torch.cuda.synchronize()
+        out = ps + [b.clone() for b in opt.state]
+        opt.close()
+        return out
+
+    monkeypatch.setenv("LOPT_GROUPS", "1")
+    ref = run()
+    monkeypatch.delenv("LOPT_GROUPS")
+    got = run()
+    assert len(ref) == len(got)
+    for a, b in zip(ref, got):
+        assert torch.equal(a.view(torch.int32), b.view(torch.int32))
