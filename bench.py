@@ -197,6 +197,9 @@ def main():
         roofline["valu_issue"] = {"achieved": ginst, "peak": VALU_ISSUE_PEAK_GINST, "unit": "G wave-instructions/s",
                                   "frac": ginst / VALU_ISSUE_PEAK_GINST,
                                   "note": "executed vector instructions per 64 elements x rounds / launch time"}
+        roofline["binding_resource"] = ("vector-instruction issue (valu_issue.frac): the matrix unit is busy about 43 % of the "
+                                        "launch, HBM about 29 %; `frac` prices the algorithmic MLP FLOPs against the fp16 "
+                                        "matrix peak because that is the unit the contraction runs on")
     if bound == "mfma":
         # the same algorithmic FLOP rate against the fp32 vector-ALU peak (what a kernel without matrix cores could reach)
         roofline["frac_of_fp32_vector_peak"] = achieved / MFMA_F32_PEAK_TFLOPS
