@@ -13,7 +13,7 @@
  *    workspace are DEVICE memory owned by the caller (fp32, 16-byte aligned).
  *  - The library owns only the lopt_ctx: a device copy of the optimizer's weights,
  *    a cached device table describing the tensor list, a pinned staging buffer and
- *    one extra stream with its events.
+ *    one extra stream with its events (plus one fixed scratch array per GPU, see lopt_step_static).
  *    lopt_step allocates device memory only when the tensor list changes.
  *  - All device work is ordered by the HIP stream passed in (a hipStream_t cast to
  *    void*, NULL = default stream): it starts after everything enqueued on that
@@ -57,7 +57,8 @@ typedef enum {
   LOPT_ESHAPE = 2, /* rows/cols out of range */
   LOPT_ESTATE = 3, /* weights blob of the wrong size for this configuration */
   LOPT_ENOMEM = 4, /* host or device allocation failed */
-  LOPT_EHIP = 5    /* a HIP runtime call failed (message has the HIP error string) */
+  LOPT_EHIP = 5,   /* a HIP runtime call failed (message has the HIP error string) */
+  LOPT_ELIMIT = 6  /* lopt_step_static: the tensor list needs more scratch than the fixed array holds */
 } lopt_status;
 
 typedef enum { LOPT_SMALL_FC = 0, LOPT_VELO = 1 } lopt_kind;
@@ -163,6 +164,27 @@ lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs_hos
                       float* const* params_host, const float* const* grads_host,
                       void* const* state_host, void* workspace, int64_t step, float lr,
                       float weight_decay, void* hip_stream);
+
+/* lopt_step for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc. Same arguments, semantics and results as lopt_step, minus the
+ * workspace: the device tables and the workspace live in a fixed array of LOPT_STATIC_SCRATCH_BYTES bytes
+ * that is part of the library's device image (every GPU the library runs on holds its own copy until the
+ * process ends; its address on a device is resolved once, in lopt_create). The call makes no hipMalloc,
+ * hipFree, hipHostMalloc or event creation: tables are staged through the pinned buffer every context is
+ * created with (4 MiB).
+ *   - A list whose tables plus workspace exceed the array, or whose tables exceed the staging buffer, is
+ *     refused with LOPT_ELIMIT before anything is launched (the message gives both sizes). The ViT-B/16
+ *     parameter set (152 tensors, 86.6 M elements) needs about 12 MiB.
+ *   - Nothing in the array has to start at zero (the apply pass's tile counters are cleared inside every
+ *     step) and nothing in it survives a call: all calls on one GPU, through any context, share it. Calls
+ *     that overlap on one GPU (different streams, different host threads) race; calls ordered on one
+ *     stream are safe, and a context re-sends its tables after another context has used the array.
+ *   - Per-pass timing (lopt_profile_enable) does not apply to this entry point. */
+#define LOPT_STATIC_SCRATCH_BYTES (64u << 20)
+lopt_status lopt_step_static(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs_host,
+                             float* const* params_host, const float* const* grads_host,
+                             void* const* state_host, int64_t step, float lr, float weight_decay,
+                             void* hip_stream);
 
 /* Byte offsets, inside the workspace, of each tensor's feature statistics s_f as left by the
  * last lopt_step over this list: d floats per tensor (d = 28 for small_fc_lopt, whose time

@@ -11,10 +11,12 @@ _LIB_PATH = os.environ.get("LOPT_LIB_PATH") or os.path.join(_HERE, "liblopt.so")
 LOPT_SMALL_FC = 0
 LOPT_VELO = 1
 N_PASSES = 7
-_STATUS = {0: "LOPT_OK", 1: "LOPT_EINVAL", 2: "LOPT_ESHAPE", 3: "LOPT_ESTATE", 4: "LOPT_ENOMEM", 5: "LOPT_EHIP"}
+_STATUS = {0: "LOPT_OK", 1: "LOPT_EINVAL", 2: "LOPT_ESHAPE", 3: "LOPT_ESTATE", 4: "LOPT_ENOMEM", 5: "LOPT_EHIP",
+           6: "LOPT_ELIMIT"}
+STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = ["lopt_default_config", "lopt_weights_count", "lopt_create", "lopt_destroy", "lopt_state_bytes",
-           "lopt_init_state", "lopt_step", "lopt_stats_offsets", "lopt_last_error",
+           "lopt_init_state", "lopt_step", "lopt_step_static", "lopt_stats_offsets", "lopt_last_error",
            "lopt_profile_enable", "lopt_profile_read", "lopt_pass_name"]
 
 
@@ -66,6 +68,9 @@ def lib() -> C.CDLL:
     L.lopt_step.argtypes = [vp, sz, C.POINTER(lopt_tensor_desc), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
                             vp, C.c_int64, C.c_float, C.c_float, vp]
     L.lopt_step.restype = C.c_int
+    L.lopt_step_static.argtypes = [vp, sz, C.POINTER(lopt_tensor_desc), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
+                                   C.c_int64, C.c_float, C.c_float, vp]
+    L.lopt_step_static.restype = C.c_int
     L.lopt_stats_offsets.argtypes = [vp, sz, C.POINTER(lopt_tensor_desc), C.POINTER(sz)]
     L.lopt_stats_offsets.restype = C.c_int
     L.lopt_profile_enable.argtypes = [vp, C.c_int]
@@ -140,15 +145,20 @@ class LearnedOptimizer:
         self.step_count = 0
 
     def step(self, params: List, grads: List, lr: float = 1.0, weight_decay: float = 0.0,
-             step: Optional[int] = None):
+             step: Optional[int] = None, static: bool = False):
+        """lopt_step, or lopt_step_static (library-owned fixed scratch, no allocation) with static=True."""
         assert len(params) == self.n and len(grads) == self.n
         pp = (C.c_void_p * max(self.n, 1))(*[p.data_ptr() for p in params])
         gp = (C.c_void_p * max(self.n, 1))(*[g.data_ptr() for g in grads])
         t = self.step_count if step is None else step
         with self._torch.cuda.device(self.device):
-            _check(lib().lopt_step(self._ctx, self.n, self._descs, pp, gp, self._state_ptrs,
-                                   C.c_void_p(self.workspace.data_ptr()), t, lr, weight_decay,
-                                   self._stream()), self._ctx)
+            if static:
+                _check(lib().lopt_step_static(self._ctx, self.n, self._descs, pp, gp, self._state_ptrs, t, lr,
+                                              weight_decay, self._stream()), self._ctx)
+            else:
+                _check(lib().lopt_step(self._ctx, self.n, self._descs, pp, gp, self._state_ptrs,
+                                       C.c_void_p(self.workspace.data_ptr()), t, lr, weight_decay,
+                                       self._stream()), self._ctx)
         self.step_count = t + 1
 
     def profile_enable(self, on: bool = True):

@@ -1,10 +1,12 @@
 // Host side of the C boundary declared in include/lopt.h: argument validation, the planner that
 // turns a tensor list into the device tables the kernels walk, and the launch sequence of a step.
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -17,6 +19,18 @@ namespace {
 thread_local std::string g_last_error;
 
 constexpr int kMaxGroups = 16;
+
+// ---- fixed scratch of lopt_step_static: device tables followed by the workspace. One copy per GPU, at an address
+// of its own on each; host code reaches it only through the pointer hipGetSymbolAddress returns for the current
+// device (the array's name is a host-side stand-in, not a device address).
+constexpr size_t kStaticScratchBytes = LOPT_STATIC_SCRATCH_BYTES;
+constexpr size_t kStageInitBytes = 4u << 20;   // pinned staging every context starts with (tables of ~100 k tiles)
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices];        // per device: address of `scratch` there (null until a context is created on it)
+uint64_t g_scratch_owner[kMaxDevices];   // per device: id of the context whose tables the array holds (0 = none)
+std::atomic<uint64_t> g_next_ctx_id{1};
 
 inline uint32_t pad4(uint64_t x) { return (uint32_t)((x + 3) & ~(uint64_t)3); }
 inline uint64_t align64(uint64_t x) { return (x + 63) & ~(uint64_t)63; }
@@ -48,6 +62,20 @@ bool config_ok(const lopt_config* c, std::string* why) {
   return true;
 }
 
+// Device copy of the plan's tables and what it currently holds.
+struct TableStore {
+  char* base = nullptr;
+  size_t cap = 0;
+  bool growable = false;           // library-allocated (may be reallocated) or a fixed region
+  TensorDev* d_tensors = nullptr;
+  TileDev* d_tiles = nullptr;
+  RcItemDev* d_rcitems = nullptr;
+  ApplyTileDev* d_atiles = nullptr;
+  bool static_uploaded = false;    // tiles, row/column blocks and apply tiles are on the device
+  bool tensors_uploaded = false;
+  std::vector<TensorDev> last_tensors;  // what d_tensors currently holds
+};
+
 struct Plan {
   std::vector<lopt_tensor_desc> descs;
   std::vector<TensorDev> tensors;   // pointers filled per call
@@ -72,18 +100,13 @@ struct lopt_ctx {
   float* d_weights = nullptr;      // the uploaded blob
   float* d_tail = nullptr;         // small_fc_lopt: padded W2 b2 W3 b3
   WeightsDev W{};
-  // cached plan + device tables
+  // cached plan + device tables: `heap` is library-allocated and grows with the list, `fixed` is the front of the
+  // file-scope scratch array (lopt_step_static)
   Plan plan;
   bool plan_valid = false;
-  void* d_tables = nullptr;
-  size_t d_tables_bytes = 0;
-  TensorDev* d_tensors = nullptr;
-  TileDev* d_tiles = nullptr;
-  RcItemDev* d_rcitems = nullptr;
-  ApplyTileDev* d_atiles = nullptr;
-  bool static_uploaded = false;    // tiles + rcitems are on the device
-  std::vector<TensorDev> last_tensors;  // what d_tensors currently holds
-  bool tensors_uploaded = false;
+  TableStore heap, fixed;
+  uint64_t id = 0;                 // names this context as the owner of the static scratch's contents
+  void* static_scratch = nullptr;  // device address of `scratch` on ctx->device
   void* h_stage = nullptr;         // pinned staging
   size_t h_stage_bytes = 0;
   hipEvent_t stage_ev = nullptr;
@@ -273,60 +296,68 @@ lopt_status ensure_plan(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* d) {
     return fail(ctx, LOPT_ENOMEM, "out of host memory while planning");
   }
   ctx->plan_valid = true;
-  ctx->static_uploaded = false;
-  ctx->tensors_uploaded = false;
+  for (TableStore* st : {&ctx->heap, &ctx->fixed}) st->static_uploaded = st->tensors_uploaded = false;
   return LOPT_OK;
 }
 
-// Make sure the device tables exist and hold the current plan and pointers.
-lopt_status upload_tables(lopt_ctx* ctx, hipStream_t stream) {
+size_t table_bytes(const Plan& pl) {
+  return align64(pl.tensors.size() * sizeof(TensorDev)) + align64(pl.tiles.size() * sizeof(TileDev)) +
+         align64(pl.rcitems.size() * sizeof(RcItemDev)) + align64(pl.atiles.size() * sizeof(ApplyTileDev));
+}
+
+// Make sure the device tables of `st` hold the current plan and pointers. A growable store and the pinned staging
+// buffer are reallocated when the list outgrows them; a fixed store never allocates (the caller has checked that the
+// tables fit both).
+lopt_status upload_tables(lopt_ctx* ctx, TableStore& st, hipStream_t stream) {
   Plan& pl = ctx->plan;
   const size_t nT = pl.tensors.size(), nTi = pl.tiles.size(), nRc = pl.rcitems.size(), nAt = pl.atiles.size();
   const size_t bT = align64(nT * sizeof(TensorDev)), bTi = align64(nTi * sizeof(TileDev)),
                bRc = align64(nRc * sizeof(RcItemDev)), bAt = align64(nAt * sizeof(ApplyTileDev));
   const size_t need = bT + bTi + bRc + bAt;
   if (need == 0) return LOPT_OK;
-  if (need > ctx->d_tables_bytes) {
+  if (need > st.cap) {
+    if (!st.growable) return fail(ctx, LOPT_ELIMIT, "device tables do not fit the fixed scratch region");
     if (ctx->stage_pending) { HIP_TRY(ctx, hipEventSynchronize(ctx->stage_ev)); ctx->stage_pending = false; }
-    if (ctx->d_tables) { HIP_TRY(ctx, hipStreamSynchronize(stream)); HIP_TRY(ctx, hipFree(ctx->d_tables)); ctx->d_tables = nullptr; }
-    ctx->d_tables_bytes = 0;
-    HIP_TRY(ctx, hipMalloc(&ctx->d_tables, need));
-    ctx->d_tables_bytes = need;
-    ctx->static_uploaded = false;
-    ctx->tensors_uploaded = false;
+    if (st.base) { HIP_TRY(ctx, hipStreamSynchronize(stream)); HIP_TRY(ctx, hipFree(st.base)); st.base = nullptr; }
+    st.cap = 0;
+    HIP_TRY(ctx, hipMalloc((void**)&st.base, need));
+    st.cap = need;
+    st.static_uploaded = false;
+    st.tensors_uploaded = false;
   }
   if (need > ctx->h_stage_bytes) {
+    if (!st.growable) return fail(ctx, LOPT_ELIMIT, "device tables do not fit the pinned staging buffer");
     if (ctx->stage_pending) { HIP_TRY(ctx, hipEventSynchronize(ctx->stage_ev)); ctx->stage_pending = false; }
     if (ctx->h_stage) { HIP_TRY(ctx, hipHostFree(ctx->h_stage)); ctx->h_stage = nullptr; }
     ctx->h_stage_bytes = 0;
     HIP_TRY(ctx, hipHostMalloc(&ctx->h_stage, need, hipHostMallocDefault));
     ctx->h_stage_bytes = need;
   }
-  char* dbase = (char*)ctx->d_tables;
-  ctx->d_tensors = (TensorDev*)dbase;
-  ctx->d_tiles = (TileDev*)(dbase + bT);
-  ctx->d_rcitems = (RcItemDev*)(dbase + bT + bTi);
-  ctx->d_atiles = (ApplyTileDev*)(dbase + bT + bTi + bRc);
-  const bool need_tensors = !ctx->tensors_uploaded || ctx->last_tensors.size() != nT ||
-                            memcmp(ctx->last_tensors.data(), pl.tensors.data(), nT * sizeof(TensorDev)) != 0;
-  const bool need_static = !ctx->static_uploaded;
+  char* dbase = st.base;
+  st.d_tensors = (TensorDev*)dbase;
+  st.d_tiles = (TileDev*)(dbase + bT);
+  st.d_rcitems = (RcItemDev*)(dbase + bT + bTi);
+  st.d_atiles = (ApplyTileDev*)(dbase + bT + bTi + bRc);
+  const bool need_tensors = !st.tensors_uploaded || st.last_tensors.size() != nT ||
+                            memcmp(st.last_tensors.data(), pl.tensors.data(), nT * sizeof(TensorDev)) != 0;
+  const bool need_static = !st.static_uploaded;
   if (!need_tensors && !need_static) return LOPT_OK;
   if (ctx->stage_pending) { HIP_TRY(ctx, hipEventSynchronize(ctx->stage_ev)); ctx->stage_pending = false; }
   char* hbase = (char*)ctx->h_stage;
   if (need_tensors) {
     memcpy(hbase, pl.tensors.data(), nT * sizeof(TensorDev));
-    HIP_TRY(ctx, hipMemcpyAsync(ctx->d_tensors, hbase, nT * sizeof(TensorDev), hipMemcpyHostToDevice, stream));
-    ctx->last_tensors = pl.tensors;
-    ctx->tensors_uploaded = true;
+    HIP_TRY(ctx, hipMemcpyAsync(st.d_tensors, hbase, nT * sizeof(TensorDev), hipMemcpyHostToDevice, stream));
+    st.last_tensors = pl.tensors;
+    st.tensors_uploaded = true;
   }
   if (need_static) {
     memcpy(hbase + bT, pl.tiles.data(), nTi * sizeof(TileDev));
     memcpy(hbase + bT + bTi, pl.rcitems.data(), nRc * sizeof(RcItemDev));
-    HIP_TRY(ctx, hipMemcpyAsync(ctx->d_tiles, hbase + bT, nTi * sizeof(TileDev) , hipMemcpyHostToDevice, stream));
-    if (nRc) HIP_TRY(ctx, hipMemcpyAsync(ctx->d_rcitems, hbase + bT + bTi, nRc * sizeof(RcItemDev), hipMemcpyHostToDevice, stream));
+    HIP_TRY(ctx, hipMemcpyAsync(st.d_tiles, hbase + bT, nTi * sizeof(TileDev) , hipMemcpyHostToDevice, stream));
+    if (nRc) HIP_TRY(ctx, hipMemcpyAsync(st.d_rcitems, hbase + bT + bTi, nRc * sizeof(RcItemDev), hipMemcpyHostToDevice, stream));
     memcpy(hbase + bT + bTi + bRc, pl.atiles.data(), nAt * sizeof(ApplyTileDev));
-    if (nAt) HIP_TRY(ctx, hipMemcpyAsync(ctx->d_atiles, hbase + bT + bTi + bRc, nAt * sizeof(ApplyTileDev), hipMemcpyHostToDevice, stream));
-    ctx->static_uploaded = true;
+    if (nAt) HIP_TRY(ctx, hipMemcpyAsync(st.d_atiles, hbase + bT + bTi + bRc, nAt * sizeof(ApplyTileDev), hipMemcpyHostToDevice, stream));
+    st.static_uploaded = true;
   }
   HIP_TRY(ctx, hipEventRecord(ctx->stage_ev, stream));
   ctx->stage_pending = true;
@@ -419,6 +450,21 @@ lopt_status lopt_create(const lopt_config* cfg, const float* weights_host, size_
   CREATE_TRY(hipMalloc((void**)&ctx->d_weights, n_weights * sizeof(float)));
   CREATE_TRY(hipMemcpy(ctx->d_weights, weights_host, n_weights * sizeof(float), hipMemcpyHostToDevice));
   CREATE_TRY(hipEventCreateWithFlags(&ctx->stage_ev, hipEventDisableTiming));
+  CREATE_TRY(hipHostMalloc(&ctx->h_stage, kStageInitBytes, hipHostMallocDefault));
+  ctx->h_stage_bytes = kStageInitBytes;
+  ctx->heap.growable = true;
+  ctx->id = g_next_ctx_id.fetch_add(1);
+  if (ctx->device >= 0 && ctx->device < kMaxDevices) {
+    // the fixed scratch of lopt_step_static: resolve this device's copy once, with this device current
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[ctx->device]) {
+      void* sp = nullptr;
+      CREATE_TRY(hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch)));
+      g_scratch_ptr[ctx->device] = sp;
+    }
+    ctx->static_scratch = g_scratch_ptr[ctx->device];
+    ctx->fixed.base = (char*)ctx->static_scratch;
+  }
   {
     CREATE_TRY(hipStreamCreateWithFlags(&ctx->aux_stream, hipStreamNonBlocking));
     CREATE_TRY(hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming));
@@ -471,7 +517,7 @@ void lopt_destroy(lopt_ctx* ctx) {
   if (!ctx) return;
   if (ctx->d_weights) (void)hipFree(ctx->d_weights);
   if (ctx->d_tail) (void)hipFree(ctx->d_tail);
-  if (ctx->d_tables) (void)hipFree(ctx->d_tables);
+  if (ctx->heap.base) (void)hipFree(ctx->heap.base);
   if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
   if (ctx->stage_ev) (void)hipEventDestroy(ctx->stage_ev);
   for (hipEvent_t e : ctx->prof_events) (void)hipEventDestroy(e);
@@ -540,19 +586,24 @@ lopt_status lopt_init_state(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* des
     TensorDev& T = ctx->plan.tensors[i];
     T.st = (float*)state[i];
   }
-  st = upload_tables(ctx, stream);
+  st = upload_tables(ctx, ctx->heap, stream);
   if (st != LOPT_OK) return st;
-  Launch L{ctx->d_tensors, ctx->d_tiles, ctx->d_rcitems, nullptr, (int)n, (int)ctx->plan.tiles.size(),
-           (int)ctx->plan.rcitems.size(), ctx->d_atiles, (int)ctx->plan.atiles.size(), 0, nullptr, 0};
+  const TableStore& tb = ctx->heap;
+  Launch L{tb.d_tensors, tb.d_tiles, tb.d_rcitems, nullptr, (int)n, (int)ctx->plan.tiles.size(),
+           (int)ctx->plan.rcitems.size(), tb.d_atiles, (int)ctx->plan.atiles.size(), 0, nullptr, 0};
   StepArgs A = make_args(ctx, 0, 0.f, 0.f, (int)n);
   launch_fill_zero(L, A, stream);
   HIP_TRY(ctx, hipGetLastError());
   return LOPT_OK;
 }
 
-lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, float* const* params,
-                      const float* const* grads, void* const* state, void* workspace, int64_t step, float lr,
-                      float weight_decay, void* hip_stream) {
+}  // extern "C"
+
+// One step. use_static: tables and workspace live in the file-scope scratch array of this device (`workspace` is
+// ignored) and nothing on this path allocates.
+static lopt_status step_impl(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, float* const* params,
+                             const float* const* grads, void* const* state, void* workspace, int64_t step, float lr,
+                             float weight_decay, void* hip_stream, bool use_static) {
   if (!ctx) return fail(nullptr, LOPT_EINVAL, "ctx is null");
   lopt_status st = check_descs(ctx, n, descs);
   if (st != LOPT_OK) return st;
@@ -562,22 +613,45 @@ lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, fl
   if ((st = check_ptrs(ctx, n, (const void* const*)grads, "grads_host")) != LOPT_OK) return st;
   if ((st = check_ptrs(ctx, n, (const void* const*)state, "state_host")) != LOPT_OK) return st;
   if (n == 0) return LOPT_OK;
-  if (!workspace) return fail(ctx, LOPT_EINVAL, "workspace is null");
-  if ((uintptr_t)workspace & 15) return fail(ctx, LOPT_EINVAL, "workspace is not 16-byte aligned");
+  if (use_static) {
+    if (!ctx->static_scratch) return fail(ctx, LOPT_EINVAL, "no static scratch on this device");
+  } else {
+    if (!workspace) return fail(ctx, LOPT_EINVAL, "workspace is null");
+    if ((uintptr_t)workspace & 15) return fail(ctx, LOPT_EINVAL, "workspace is not 16-byte aligned");
+  }
   if ((st = ensure_plan(ctx, n, descs)) != LOPT_OK) return st;
   hipStream_t stream = (hipStream_t)hip_stream;
   Plan& pl = ctx->plan;
+  TableStore& tb = use_static ? ctx->fixed : ctx->heap;
+  if (use_static) {
+    // layout of the array: [tables, rounded up to 256 bytes | workspace]
+    const size_t tbytes = (table_bytes(pl) + 255) & ~(size_t)255;
+    const size_t need = tbytes + (size_t)pl.ws_floats * sizeof(float);
+    if (need > kStaticScratchBytes || table_bytes(pl) > ctx->h_stage_bytes) {
+      char buf[200];
+      snprintf(buf, sizeof buf, "this tensor list needs %zu bytes of scratch (%zu of them tables); lopt_step_static has %zu "
+               "(tables: %zu)", need, table_bytes(pl), kStaticScratchBytes, ctx->h_stage_bytes);
+      return fail(ctx, LOPT_ELIMIT, buf);
+    }
+    tb.cap = tbytes;
+    workspace = ctx->fixed.base + tbytes;
+    // another context may have used the array since this one last did: then nothing of ours is left in it
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (g_scratch_owner[ctx->device] != ctx->id) tb.static_uploaded = tb.tensors_uploaded = false;
+    g_scratch_owner[ctx->device] = ctx->id;
+  }
   for (size_t i = 0; i < n; ++i) {
     TensorDev& T = pl.tensors[i];
     T.p = params[i];
     T.g = grads[i];
     T.st = (float*)state[i];
   }
-  if ((st = upload_tables(ctx, stream)) != LOPT_OK) return st;
+  if ((st = upload_tables(ctx, tb, stream)) != LOPT_OK) return st;
   // workspace base rounded up to 256 bytes (lopt_state_bytes adds the slack)
   float* ws = (float*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255);
-  Launch L{ctx->d_tensors, ctx->d_tiles, ctx->d_rcitems, ws, (int)n, (int)pl.tiles.size(), (int)pl.rcitems.size(),
-           ctx->d_atiles, (int)pl.atiles.size(), 0, (int*)(ws + pl.oCounters), 2 * ctx->n_cu};
+  Launch L{tb.d_tensors, tb.d_tiles, tb.d_rcitems, ws, (int)n, (int)pl.tiles.size(), (int)pl.rcitems.size(),
+           tb.d_atiles, (int)pl.atiles.size(), 0, (int*)(ws + pl.oCounters), 2 * ctx->n_cu};
+  const bool profiling = ctx->profiling && !use_static;   // per-pass timing creates events: not on the static path
   StepArgs A = make_args(ctx, step, lr, weight_decay, (int)n);
   const bool mfma_ok = apply_mfma_available(A);
   // the strip-form kernel addresses a row pair with 32-bit byte offsets
@@ -596,7 +670,7 @@ lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, fl
   // pay for the extra launches, and per-pass timing is off (its events assume one pass after the other)
   int G = 1;
   const bool velo = ctx->cfg.kind == LOPT_VELO;
-  if (ctx->aux_stream && !ctx->profiling) {
+  if (ctx->aux_stream && !profiling) {
     if (strip_ok) G = planned_groups(ctx->groups_override, pl.total_elems, n);
     else if (velo && ctx->groups_override) G = planned_groups(ctx->groups_override, pl.total_elems, n);
   }
@@ -649,7 +723,7 @@ lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, fl
     return LOPT_OK;
   }
   hipEvent_t* ev = nullptr;
-  if (ctx->profiling) {
+  if (profiling) {
     const size_t need = (ctx->prof_steps + 1) * (LOPT_N_PASSES + 1);
     while (ctx->prof_events.size() < need) {
       hipEvent_t e;
@@ -683,6 +757,20 @@ lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, fl
 #undef MARK
   HIP_TRY(ctx, hipGetLastError());
   return LOPT_OK;
+}
+
+extern "C" {
+
+lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, float* const* params,
+                      const float* const* grads, void* const* state, void* workspace, int64_t step, float lr,
+                      float weight_decay, void* hip_stream) {
+  return step_impl(ctx, n, descs, params, grads, state, workspace, step, lr, weight_decay, hip_stream, false);
+}
+
+lopt_status lopt_step_static(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs, float* const* params,
+                             const float* const* grads, void* const* state, int64_t step, float lr,
+                             float weight_decay, void* hip_stream) {
+  return step_impl(ctx, n, descs, params, grads, state, nullptr, step, lr, weight_decay, hip_stream, true);
 }
 
 lopt_status lopt_profile_enable(lopt_ctx* ctx, int on) {
