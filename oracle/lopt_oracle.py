@@ -24,9 +24,15 @@ Readings taken where the paper is silent (each is a documented choice):
     weight decay is decoupled: p <- p - lr * (delta + wd * p_old);
   * 1-D tensors are 1 x n matrices.
   * the VeLO per-tensor LSTM hypernetwork is not described by the paper at all;
-    `velo_hypernetwork` below is this project's definition of it.
+    `velo_hypernetwork` below is this project's definition of it. What the paper
+    does fix is that VeLO's step takes the current loss value (artifact appendix,
+    "Basic Usage"): the loss enters the hypernetwork's input through
+    `loss_features`. The definition also has a cross-tensor term (the mean of the
+    tensors' previous LSTM outputs is an input of every tensor's LSTM) and a
+    per-tensor step-size output.
     Fidelity of that part to the original VeLO: PARITY UNPINNED (no weights, no
-    worked example); it is pinned only against torch.nn.LSTMCell and brute force.
+    worked example); it is pinned only against torch.nn.LSTMCell, closed forms
+    and brute force.
   * End-to-end agreement with the paper's released optimizers: PARITY UNPINNED
     (the paper prints no worked numeric example).
 
@@ -49,6 +55,8 @@ F64 = np.float64
 TIME_SCALES = (1.0, 3.0, 10.0, 30.0, 100.0, 300.0, 1000.0, 3000.0, 1e4, 3e4, 1e5)
 # Clip bound of VeLO's clipped-gradient feature: VeLO feature table, row "Clipped gradient value".
 GRAD_CLIP = 0.1
+# Scales of the loss features tanh(psi(loss)/x) (project-defined, see loss_features).
+LOSS_SCALES = (1.0, 3.0, 10.0)
 N_ELEM = 28           # per-element features shared by both optimizers
 KIND_SMALL_FC = "small_fc_lopt"
 KIND_VELO = "velo"
@@ -223,10 +231,16 @@ def _sigmoid(x):
     return 1.0 / (1.0 + np.exp(-x))
 
 
+def velo_input_size() -> int:
+    """29 log-statistics + 11 time features + one-hot(min(ndim, 4)) + 3 loss features."""
+    return (N_ELEM + 1) + len(TIME_SCALES) + 5 + len(LOSS_SCALES)
+
+
 def unpack_velo(weights: np.ndarray, cfg: OracleConfig):
+    """weights = Wx[48,4HL] | Wh[HL,4HL] | Wg[HL,4HL] | b[4HL] | Wa[HL,K] | ba[K] | ws[HL] | bs[1] | B[K,P]."""
     w = np.asarray(weights, F64).ravel()
     HL, K, H = cfg.lstm_hidden, cfg.n_bank, cfg.hidden
-    n_in = (N_ELEM + 1) + len(TIME_SCALES) + 5
+    n_in = velo_input_size()
     n_theta = (N_ELEM + 1) * H + H + H * H + H + 2 * H + 2
     o = 0
 
@@ -237,10 +251,10 @@ def unpack_velo(weights: np.ndarray, cfg: OracleConfig):
         o += n
         return v
 
-    Wx = take(n_in, 4 * HL); Wh = take(HL, 4 * HL); b = take(4 * HL)
-    Wa = take(HL, K); ba = take(K); B = take(K, n_theta)
+    Wx = take(n_in, 4 * HL); Wh = take(HL, 4 * HL); Wg = take(HL, 4 * HL); b = take(4 * HL)
+    Wa = take(HL, K); ba = take(K); ws = take(HL); bs = take(1); B = take(K, n_theta)
     assert o == w.size, (o, w.size)
-    return Wx, Wh, b, Wa, ba, B
+    return Wx, Wh, Wg, b, Wa, ba, ws, bs, B
 
 
 def lstm_cell(u, h, c, Wx, Wh, b):
@@ -253,21 +267,41 @@ def lstm_cell(u, h, c, Wx, Wh, b):
     return h_new, c_new
 
 
-def velo_hypernetwork(s: np.ndarray, t: int, ndim: int, st, weights, cfg: OracleConfig) -> np.ndarray:
-    """Per-tensor MLP weights for this step (project-defined; see module header).
+def loss_features(loss: float) -> np.ndarray:
+    """The loss value handed to VeLO's step (artifact appendix, "Basic Usage") as hypernetwork inputs:
+    tanh(psi / x) for x in LOSS_SCALES with psi = sign(loss) * ln(1 + |loss|). Bounded, odd in the loss,
+    zero for a loss of zero (which is also what a step without a loss value means)."""
+    psi = np.sign(F64(loss)) * np.log1p(abs(F64(loss)))
+    return np.tanh(psi / np.asarray(LOSS_SCALES, F64))
+
+
+def mean_hidden(hs) -> np.ndarray:
+    """Cross-tensor term: mean over the tensors of the step's list of their LSTM outputs h from the
+    previous step (zeros before the first step)."""
+    hs = [np.asarray(h, F64) for h in hs]
+    return np.sum(hs, axis=0) / len(hs)
+
+
+def velo_hypernetwork(s: np.ndarray, t: int, ndim: int, st, weights, cfg: OracleConfig,
+                      loss: float = 0.0, h_mix=None):
+    """Per-tensor MLP weights and step-size multiplier for this step (project-defined; see module header).
 
     input u = [0.05*ln(s_f + 1e-30) for the 29 statistics] ++ [11 time features]
-              ++ one_hot(min(ndim, 4), 5);
-    (h, c) <- LSTMCell(u, (h, c)); alpha = h W_a + b_a; theta = alpha @ B.
-    """
-    Wx, Wh, b, Wa, ba, B = unpack_velo(weights, cfg)
+              ++ one_hot(min(ndim, 4), 5) ++ loss_features(loss);
+    (h, c) <- LSTMCell(u, (h, c)) with the extra input term h_mix @ Wg, h_mix = mean_hidden over the list
+    (None: a list of this tensor alone, so h_mix is its own previous h);
+    alpha = h W_a + b_a; theta = alpha @ B; lam = exp(h . w_s + b_s).
+    Returns (theta, lam)."""
+    Wx, Wh, Wg, b, Wa, ba, ws, bs, B = unpack_velo(weights, cfg)
     onehot = np.zeros(5, F64)
     onehot[min(int(ndim), 4)] = 1.0
-    u = np.concatenate([0.05 * np.log(s[:N_ELEM + 1] + _f32(1e-30)), time_features(t), onehot])
-    h, c = lstm_cell(u, st["h"], st["cl"], Wx, Wh, b)
+    u = np.concatenate([0.05 * np.log(s[:N_ELEM + 1] + _f32(1e-30)), time_features(t), onehot, loss_features(loss)])
+    hm = st["h"] if h_mix is None else np.asarray(h_mix, F64)
+    h, c = lstm_cell(u, st["h"], st["cl"], Wx, Wh, b + hm @ Wg)
     st["h"], st["cl"] = h, c
     alpha = h @ Wa + ba
-    return alpha @ B
+    lam = float(np.exp(h @ ws + bs[0]))
+    return alpha @ B, lam
 
 
 # --------------------------------------------------------------------------- one step of one tensor
@@ -283,9 +317,11 @@ def tensor_statistics(p, g, st, cfg: OracleConfig, t: int, max_chunk_elems: int 
 
 
 def tensor_step(p, g, st, weights, cfg: OracleConfig, t: int, lr: float, wd: float,
-                ndim: int = 2, max_chunk_elems: int = 1 << 19, out: Optional[dict] = None) -> np.ndarray:
+                ndim: int = 2, max_chunk_elems: int = 1 << 19, out: Optional[dict] = None,
+                loss: float = 0.0, h_mix=None) -> np.ndarray:
     """One optimizer step of one tensor; returns the new parameters (float64) and
-    updates `st` in place. `out`, if given, receives intermediate results."""
+    updates `st` in place. `out`, if given, receives intermediate results. VeLO: `loss` is the loss value
+    passed to the step, `h_mix` the mean_hidden of the step's tensor list (None: this tensor alone)."""
     p = np.asarray(p, F64)
     g = np.asarray(g, F64)
     m, n = g.shape
@@ -296,10 +332,14 @@ def tensor_step(p, g, st, weights, cfg: OracleConfig, t: int, lr: float, wd: flo
     else:
         F = None
         s = tensor_statistics(p, g, st, cfg, t, max_chunk_elems)
-    theta = weights if cfg.kind == KIND_SMALL_FC else velo_hypernetwork(s, t, ndim, st, weights, cfg)
+    if cfg.kind == KIND_SMALL_FC:
+        theta, lam = weights, 1.0
+    else:
+        theta, lam = velo_hypernetwork(s, t, ndim, st, weights, cfg, loss, h_mix)
     if out is not None:
         out["stats"] = s.copy()
         out["theta"] = np.array(theta, F64)
+        out["lam"] = lam
     p_new = np.empty_like(p)
     rows_per = m if F is not None else max(1, max_chunk_elems // max(n, 1))
     for r0 in range(0, m, rows_per):
@@ -307,21 +347,32 @@ def tensor_step(p, g, st, weights, cfg: OracleConfig, t: int, lr: float, wd: flo
         Fc = F if F is not None else construct_features(p, g, st, cfg, t, sl)
         Fn = feature_normalization(Fc, s, cfg)
         direction, magnitude = apply_lo(Fn, theta, cfg)
-        delta = delta_theta(direction, magnitude, cfg).reshape(-1, n)
+        delta = lam * delta_theta(direction, magnitude, cfg).reshape(-1, n)
         p_new[sl] = p[sl] - lr * (delta + wd * p[sl])
     return p_new
 
 
-def apply_rows(p, g, st, s, theta, cfg: OracleConfig, t: int, lr: float, wd: float, rows: slice) -> np.ndarray:
-    """New parameters of a slab of rows only, given the whole tensor's statistics `s` and the MLP
-    weights `theta` (accumulators in `st` already updated): the second half of tensor_step, for
-    spot checks on tensors too large to evaluate in full."""
+def list_step(ps, gs, sts, weights, cfg: OracleConfig, t: int, lr: float, wd: float, ndims,
+              loss: float = 0.0, outs=None):
+    """One optimizer step over a list of tensors (what one call of the optimizer's step covers): for VeLO the
+    cross-tensor term is taken over this list, before any tensor's LSTM state moves."""
+    h_mix = mean_hidden([st["h"] for st in sts]) if cfg.kind == KIND_VELO and len(sts) else None
+    return [tensor_step(ps[i], gs[i], sts[i], weights, cfg, t, lr, wd, ndim=ndims[i],
+                        out=None if outs is None else outs[i], loss=loss, h_mix=h_mix)
+            for i in range(len(ps))]
+
+
+def apply_rows(p, g, st, s, theta, cfg: OracleConfig, t: int, lr: float, wd: float, rows: slice,
+               lam: float = 1.0) -> np.ndarray:
+    """New parameters of a slab of rows only, given the whole tensor's statistics `s`, the MLP
+    weights `theta` and the step-size multiplier `lam` (accumulators in `st` already updated): the
+    second half of tensor_step, for spot checks on tensors too large to evaluate in full."""
     p = np.asarray(p, F64)
     n = p.shape[1]
     Fc = construct_features(p, g, st, cfg, t, rows)
     Fn = feature_normalization(Fc, s, cfg)
     direction, magnitude = apply_lo(Fn, theta, cfg)
-    delta = delta_theta(direction, magnitude, cfg).reshape(-1, n)
+    delta = lam * delta_theta(direction, magnitude, cfg).reshape(-1, n)
     return p[rows] - lr * (delta + wd * p[rows])
 
 

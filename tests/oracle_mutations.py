@@ -149,7 +149,62 @@ def weight_decay_uses_new_parameter(O):
     _wrap(O, "tensor_step", f)
 
 
+def loss_features_dropped(O):
+    def f(orig, loss):
+        return 0.0 * orig(loss)
+    _wrap(O, "loss_features", f)
+
+
+def loss_features_not_odd(O):
+    def f(orig, loss):
+        return orig(abs(loss))
+    _wrap(O, "loss_features", f)
+
+
+def cross_tensor_term_is_a_sum(O):
+    def f(orig, hs):
+        return orig(hs) * len(hs)
+    _wrap(O, "mean_hidden", f)
+
+
+def cross_tensor_term_ignored(O):
+    def f(orig, s, t, ndim, st, weights, cfg, loss=0.0, h_mix=None):
+        return orig(s, t, ndim, st, weights, cfg, loss, None)
+    _wrap(O, "velo_hypernetwork", f)
+
+
+def cross_tensor_term_taken_after_the_state_moved(O):
+    def f(ps, gs, sts, weights, cfg, t, lr, wd, ndims, loss=0.0, outs=None):
+        res = []
+        for i in range(len(ps)):
+            h_mix = O.mean_hidden([st["h"] for st in sts]) if cfg.kind == O.KIND_VELO else None
+            res.append(O.tensor_step(ps[i], gs[i], sts[i], weights, cfg, t, lr, wd, ndim=ndims[i],
+                                     out=None if outs is None else outs[i], loss=loss, h_mix=h_mix))
+        return res
+    O.list_step = f
+
+
+def step_size_output_not_applied(O):
+    def f(orig, s, t, ndim, st, weights, cfg, loss=0.0, h_mix=None):
+        theta, lam = orig(s, t, ndim, st, weights, cfg, loss, h_mix)
+        return theta, 1.0
+    _wrap(O, "velo_hypernetwork", f)
+
+
+def step_size_scales_the_decay_too(O):
+    def f(orig, p, g, st, weights, cfg, t, lr, wd, **kw):
+        out = kw.get("out")
+        info = out if out is not None else {}
+        kw["out"] = info
+        p_new = orig(p, g, st, weights, cfg, t, lr, wd, **kw)
+        lam = info.get("lam", 1.0)
+        return p_new - lr * wd * (lam - 1.0) * np.asarray(p, float)
+    _wrap(O, "tensor_step", f)
+
+
 MUTATIONS = {f.__name__: f for f in [
+    loss_features_dropped, loss_features_not_odd, cross_tensor_term_is_a_sum, cross_tensor_term_ignored,
+    cross_tensor_term_taken_after_the_state_moved, step_size_output_not_applied, step_size_scales_the_decay_too,
     swap_row_col_axes, momentum_without_one_minus_beta, second_moment_uses_abs_instead_of_square,
     update_added_instead_of_subtracted, exp_multiplier_dropped, normalization_without_square_root,
     time_features_normalized_too, statistics_are_mean_not_mean_square, outputs_swapped, second_relu_missing,

@@ -17,6 +17,12 @@ def cfg(kind=O.KIND_SMALL_FC, **kw):
     return O.OracleConfig(kind=kind, **kw)
 
 
+def velo_size(H, HL, K):
+    """Floats in a VeLO weight blob: Wx[48,4HL] Wh[HL,4HL] Wg[HL,4HL] b[4HL] Wa[HL,K] ba[K] ws[HL] bs[1] B[K,P]."""
+    P = 29 * H + H + H * H + H + 2 * H + 2
+    return 48 * 4 * HL + 2 * HL * 4 * HL + 4 * HL + HL * K + K + HL + 1 + K * P
+
+
 def rand_state_after(steps, m, n, c, seed=0, scale=1e-3):
     rng = np.random.default_rng(seed)
     st = O.init_state(m, n, c)
@@ -223,7 +229,7 @@ def test_row_and_column_permutation_equivariance(kind):
         theta = rng.standard_normal(39 * 5 + 5 + 25 + 5 + 10 + 2) * 0.3
     else:
         n_theta = 29 * 5 + 5 + 25 + 5 + 10 + 2
-        theta = rng.standard_normal(45 * 24 + 6 * 24 + 24 + 6 * 3 + 3 + 3 * n_theta) * 0.3
+        theta = rng.standard_normal(velo_size(5, 6, 3)) * 0.3
     p0 = rng.standard_normal((m, n)) * 0.02
     gs = [rng.standard_normal((m, n)) * 1e-2 for _ in range(3)]
 
@@ -318,7 +324,7 @@ def test_weight_decay_closed_form():
 
 # ------------------------------------------------------------------ brute force, 4 x 3
 
-def _brute_force_step(p, g, M, V, r, c, theta, C, kind, t, lr, wd):
+def _brute_force_step(p, g, M, V, r, c, theta, C, kind, t, lr, wd, lam=1.0):
     """Scalar-loop implementation straight from the feature tables; lists only."""
     m, n = len(p), len(p[0])
     H = C.hidden
@@ -370,7 +376,7 @@ def _brute_force_step(p, g, M, V, r, c, theta, C, kind, t, lr, wd):
             h1 = [max(0.0, b1[u] + sum(x[q] * W1[q][u] for q in range(d))) for u in range(H)]
             h2 = [max(0.0, b2[u] + sum(h1[q] * W2[q][u] for q in range(H))) for u in range(H)]
             o2 = [b3[u] + sum(h2[q] * W3[q][u] for q in range(H)) for u in range(2)]
-            delta = o2[0] * math.exp(o2[1] * C.exp_mult) * C.step_mult
+            delta = lam * o2[0] * math.exp(o2[1] * C.exp_mult) * C.step_mult
             out[i][j] = p[i][j] - lr * (delta + wd * p[i][j])
     return out, s
 
@@ -406,7 +412,7 @@ def test_velo_mlp_part_4x3_against_scalar_brute_force():
     rng = np.random.default_rng(15)
     m, n = 4, 3
     n_theta = 29 * 2 + 2 + 4 + 2 + 4 + 2
-    weights = rng.uniform(-0.7, 0.7, 45 * 12 + 3 * 12 + 12 + 3 * 2 + 2 + 2 * n_theta)
+    weights = rng.uniform(-0.7, 0.7, velo_size(2, 3, 2))
     p = rng.standard_normal((m, n)) * 0.05
     st = O.init_state(m, n, C)
     M = [[[0.0] * n for _ in range(m)] for _ in range(3)]
@@ -418,7 +424,8 @@ def test_velo_mlp_part_4x3_against_scalar_brute_force():
         info = {}
         p_prev = p.tolist()
         p = O.tensor_step(p, g, st, weights, C, t, 0.9, 0.05, ndim=2, out=info)
-        pb, s = _brute_force_step(p_prev, g.tolist(), M, V, r, c, info["theta"], C, O.KIND_VELO, t, 0.9, 0.05)
+        pb, s = _brute_force_step(p_prev, g.tolist(), M, V, r, c, info["theta"], C, O.KIND_VELO, t, 0.9, 0.05,
+                                  lam=info["lam"])
         np.testing.assert_allclose(info["stats"], s, rtol=1e-11)
         np.testing.assert_allclose(p, np.array(pb), rtol=1e-10, atol=1e-16)
 
@@ -447,35 +454,197 @@ def test_lstm_cell_matches_torch_lstmcell():
     np.testing.assert_allclose(c2, c1[0].numpy(), rtol=1e-12)
 
 
+def _split_velo(weights, H, HL, K):
+    n_theta = 29 * H + H + H * H + H + 2 * H + 2
+    o = 0
+    out = []
+    for shape in ((48, 4 * HL), (HL, 4 * HL), (HL, 4 * HL), (4 * HL,), (HL, K), (K,), (HL,), (1,), (K, n_theta)):
+        n = int(np.prod(shape))
+        out.append(weights[o:o + n].reshape(shape))
+        o += n
+    assert o == weights.size
+    return out
+
+
 def test_velo_hypernetwork_brute_force_and_state_carry():
+    # scalar loops over the whole hypernetwork: input assembly (statistics, time, rank one-hot, loss), LSTM cell with
+    # the cross-tensor input term, bank mixing, step-size output; the state carries from call to call
     C = cfg(O.KIND_VELO, hidden=2, lstm_hidden=3, n_bank=2)
     rng = np.random.default_rng(17)
     n_theta = 29 * 2 + 2 + 4 + 2 + 4 + 2
-    weights = rng.uniform(-0.7, 0.7, 45 * 12 + 3 * 12 + 12 + 3 * 2 + 2 + 2 * n_theta)
-    Wx = weights[:45 * 12].reshape(45, 12); o = 45 * 12
-    Wh = weights[o:o + 36].reshape(3, 12); o += 36
-    b = weights[o:o + 12]; o += 12
-    Wa = weights[o:o + 6].reshape(3, 2); o += 6
-    ba = weights[o:o + 2]; o += 2
-    B = weights[o:].reshape(2, n_theta)
+    weights = rng.uniform(-0.7, 0.7, velo_size(2, 3, 2))
+    Wx, Wh, Wg, b, Wa, ba, ws, bs, B = _split_velo(weights, 2, 3, 2)
     st = O.init_state(2, 2, C)
     h = [0.0] * 3
     cl = [0.0] * 3
     sg = lambda x: 1 / (1 + math.exp(-x))
-    for t, ndim in [(0, 1), (5, 2), (9, 4), (12, 7)]:
+    for t, ndim, loss in [(0, 1, 2.5), (5, 2, 0.0), (9, 4, -0.75), (12, 7, 1e4)]:
         s = rng.uniform(1e-9, 10.0, 29)
-        theta = O.velo_hypernetwork(s, t, ndim, st, weights, C)
+        hm = rng.uniform(-1, 1, 3)
+        theta, lam = O.velo_hypernetwork(s, t, ndim, st, weights, C, loss=loss, h_mix=hm)
         u = [0.05 * math.log(v + float(np.float32(1e-30))) for v in s]
         u += [math.tanh(t / x) for x in O.TIME_SCALES]
         u += [1.0 if q == min(ndim, 4) else 0.0 for q in range(5)]
-        z = [b[q] + sum(u[a] * Wx[a][q] for a in range(45)) + sum(h[a] * Wh[a][q] for a in range(3))
-             for q in range(12)]
+        psi = math.copysign(math.log(1.0 + abs(loss)), loss) if loss != 0 else 0.0
+        u += [math.tanh(psi / x) for x in (1.0, 3.0, 10.0)]
+        assert len(u) == 48
+        z = [b[q] + sum(u[a] * Wx[a][q] for a in range(48)) + sum(h[a] * Wh[a][q] for a in range(3))
+             + sum(hm[a] * Wg[a][q] for a in range(3)) for q in range(12)]
         cl = [sg(z[3 + q]) * cl[q] + sg(z[q]) * math.tanh(z[6 + q]) for q in range(3)]
         h = [sg(z[9 + q]) * math.tanh(cl[q]) for q in range(3)]
         alpha = [ba[q] + sum(h[a] * Wa[a][q] for a in range(3)) for q in range(2)]
         expect = [sum(alpha[q] * B[q][w] for q in range(2)) for w in range(n_theta)]
         np.testing.assert_allclose(theta, expect, rtol=1e-11)
         np.testing.assert_allclose(st["h"], h, rtol=1e-12)
+        assert lam == pytest.approx(math.exp(bs[0] + sum(h[a] * ws[a] for a in range(3))), rel=1e-12)
+
+
+def test_loss_features_closed_forms():
+    # zero loss (or no loss given) contributes nothing; psi = ln(1 + loss) = 1 at loss = e - 1; odd; bounded; monotone
+    assert np.all(O.loss_features(0.0) == 0.0)
+    np.testing.assert_allclose(O.loss_features(math.e - 1.0), [math.tanh(1.0), math.tanh(1 / 3), math.tanh(0.1)], rtol=1e-13)
+    np.testing.assert_allclose(O.loss_features(-3.7), -O.loss_features(3.7), rtol=0, atol=0)
+    big = O.loss_features(1e30)
+    assert np.all(big <= 1.0) and big[0] == pytest.approx(1.0) and big[2] == pytest.approx(math.tanh(math.log(1e30) / 10), rel=1e-12)
+    xs = np.array([-50.0, -1.0, -1e-3, 0.0, 1e-3, 0.2, 3.0, 700.0])
+    f = np.stack([O.loss_features(x) for x in xs])
+    assert np.all(np.diff(f, axis=0) > 0)
+    assert len(O.LOSS_SCALES) == 3 and O.velo_input_size() == 48
+
+
+def _velo_list_case(seed, Wg_zero=False, loss_rows_zero=False):
+    C = cfg(O.KIND_VELO, hidden=3, lstm_hidden=4, n_bank=2)
+    rng = np.random.default_rng(seed)
+    w = rng.uniform(-0.6, 0.6, velo_size(3, 4, 2))
+    if Wg_zero:
+        o = 48 * 16 + 4 * 16
+        w[o:o + 4 * 16] = 0.0
+    if loss_rows_zero:
+        w[45 * 16:48 * 16] = 0.0
+    shapes = [(3, 4), (1, 5), (6, 2)]
+    ps = [rng.standard_normal(sh) * 0.03 for sh in shapes]
+    gss = [[rng.standard_normal(sh) * 0.01 for sh in shapes] for _ in range(3)]
+    return C, w, shapes, ps, gss
+
+
+def _run_list(C, w, shapes, ps, gss, order=None, losses=(0.3, 1.7, 0.9)):
+    order = list(range(len(shapes))) if order is None else order
+    ps = [ps[i].copy() for i in order]
+    sts = [O.init_state(*shapes[i], C) for i in order]
+    for t, gs in enumerate(gss):
+        ps = O.list_step(ps, [gs[i] for i in order], sts, w, C, t, 0.8, 0.01, [[2, 1, 2][i] for i in order],
+                         loss=losses[t])
+    return ps, sts
+
+
+def test_cross_tensor_term_is_the_mean_of_previous_outputs_over_the_list():
+    C, w, shapes, ps, gss = _velo_list_case(31)
+    # brute force of the mean, step by step: every tensor's LSTM sees the same vector, taken BEFORE any state moves
+    sts = [O.init_state(*sh, C) for sh in shapes]
+    cur = [p.copy() for p in ps]
+    for t, gs in enumerate(gss):
+        hbar = [sum(float(st["h"][j]) for st in sts) / len(sts) for j in range(4)]
+        np.testing.assert_allclose(O.mean_hidden([st["h"] for st in sts]), hbar, rtol=1e-14, atol=0)
+        if t == 0:
+            assert hbar == [0.0] * 4
+        ref_sts = [{k: v.copy() for k, v in st.items()} for st in sts]
+        ref = [O.tensor_step(cur[i], gs[i], ref_sts[i], w, C, t, 0.8, 0.01, ndim=[2, 1, 2][i], loss=0.4, h_mix=hbar)
+               for i in range(3)]
+        cur = O.list_step(cur, gs, sts, w, C, t, 0.8, 0.01, [2, 1, 2], loss=0.4)
+        for a, b_ in zip(cur, ref):
+            np.testing.assert_allclose(a, b_, rtol=1e-13)
+        for a, b_ in zip(sts, ref_sts):
+            np.testing.assert_allclose(a["h"], b_["h"], rtol=1e-13)
+
+
+def test_cross_tensor_term_order_invariance_and_decoupling():
+    C, w, shapes, ps, gss = _velo_list_case(32)
+    base, _ = _run_list(C, w, shapes, ps, gss)
+    # the order of the list does not matter (a mean), each tensor's own result does not move with its position
+    perm, _ = _run_list(C, w, shapes, ps, gss, order=[2, 0, 1])
+    for k, i in enumerate([2, 0, 1]):
+        np.testing.assert_allclose(perm[k], base[i], rtol=1e-12)
+    # with non-zero mixing weights the tensors are coupled: a tensor stepped alone ends elsewhere ...
+    alone = []
+    for i in range(3):
+        st = O.init_state(*shapes[i], C)
+        p = ps[i].copy()
+        for t, gs in enumerate(gss):
+            p = O.tensor_step(p, gs[i], st, w, C, t, 0.8, 0.01, ndim=[2, 1, 2][i], loss=(0.3, 1.7, 0.9)[t])
+        alone.append(p)
+    assert max(np.abs(a - b_).max() for a, b_ in zip(alone, base)) > 1e-6
+    # ... and with zero mixing weights exactly where the list run ends (the term is the only coupling)
+    C0, w0, _, _, _ = _velo_list_case(32, Wg_zero=True)
+    base0, _ = _run_list(C0, w0, shapes, ps, gss)
+    for i in range(3):
+        st = O.init_state(*shapes[i], C0)
+        p = ps[i].copy()
+        for t, gs in enumerate(gss):
+            p = O.tensor_step(p, gs[i], st, w0, C0, t, 0.8, 0.01, ndim=[2, 1, 2][i], loss=(0.3, 1.7, 0.9)[t])
+        np.testing.assert_allclose(p, base0[i], rtol=1e-13)
+
+
+def test_cross_tensor_term_is_an_extra_lstm_input_like_torch_lstmcell():
+    # h_mix @ Wg enters the gates like any other input: LSTMCell on [u | h_mix] with [Wx ; Wg] gives the same state
+    torch = pytest.importorskip("torch")
+    C = cfg(O.KIND_VELO, hidden=2, lstm_hidden=5, n_bank=2)
+    rng = np.random.default_rng(33)
+    w = rng.uniform(-0.5, 0.5, velo_size(2, 5, 2))
+    Wx, Wh, Wg, b, Wa, ba, ws, bs, B = _split_velo(w, 2, 5, 2)
+    st = O.init_state(2, 2, C)
+    st["h"] = rng.uniform(-1, 1, 5)
+    st["cl"] = rng.uniform(-1, 1, 5)
+    h0, c0 = st["h"].copy(), st["cl"].copy()
+    s = rng.uniform(1e-6, 3.0, 29)
+    hm = rng.uniform(-1, 1, 5)
+    O.velo_hypernetwork(s, 7, 2, st, w, C, loss=1.25, h_mix=hm)
+    onehot = np.zeros(5); onehot[2] = 1.0
+    u = np.concatenate([0.05 * np.log(s + float(np.float32(1e-30))), np.tanh(7.0 / np.array(O.TIME_SCALES)), onehot,
+                        np.tanh(math.log(2.25) / np.array([1.0, 3.0, 10.0])), hm])
+    cell = torch.nn.LSTMCell(53, 5).double()
+    with torch.no_grad():
+        cell.weight_ih.copy_(torch.from_numpy(np.concatenate([Wx, Wg]).T.copy()))
+        cell.weight_hh.copy_(torch.from_numpy(Wh.T.copy()))
+        cell.bias_ih.copy_(torch.from_numpy(b))
+        cell.bias_hh.zero_()
+        h1, c1 = cell(torch.from_numpy(u)[None], (torch.from_numpy(h0)[None], torch.from_numpy(c0)[None]))
+    np.testing.assert_allclose(st["h"], h1[0].numpy(), rtol=1e-12)
+    np.testing.assert_allclose(st["cl"], c1[0].numpy(), rtol=1e-12)
+
+
+def test_loss_reaches_the_update_only_through_its_input_weights():
+    C, w, shapes, ps, gss = _velo_list_case(34)
+    a, _ = _run_list(C, w, shapes, ps, gss, losses=(0.3, 1.7, 0.9))
+    b_, _ = _run_list(C, w, shapes, ps, gss, losses=(5.0, 0.01, 40.0))
+    assert max(np.abs(x - y).max() for x, y in zip(a, b_)) > 1e-7        # the loss matters ...
+    C0, w0, _, _, _ = _velo_list_case(34, loss_rows_zero=True)
+    a0, _ = _run_list(C0, w0, shapes, ps, gss, losses=(0.3, 1.7, 0.9))
+    b0, _ = _run_list(C0, w0, shapes, ps, gss, losses=(5.0, 0.01, 40.0))
+    for x, y in zip(a0, b0):                                              # ... through rows 45..47 of Wx and nothing else
+        assert np.array_equal(x, y)
+
+
+def test_step_size_output_scales_the_update_and_nothing_else():
+    # w_s = 0: lam = exp(b_s) for every tensor and step. b_s = ln 2 doubles the update p_old - p_new (no weight decay);
+    # with weight decay only the learned part doubles.
+    C = cfg(O.KIND_VELO, hidden=3, lstm_hidden=4, n_bank=2)
+    rng = np.random.default_rng(35)
+    w = rng.uniform(-0.6, 0.6, velo_size(3, 4, 2))
+    o_ws = 48 * 16 + 2 * 4 * 16 + 16 + 4 * 2 + 2
+    w[o_ws:o_ws + 4] = 0.0
+    p = rng.standard_normal((5, 4)) * 0.03
+    g = rng.standard_normal((5, 4)) * 0.01
+    res = {}
+    for bs, wd in ((0.0, 0.0), (math.log(2.0), 0.0), (0.0, 0.1), (math.log(2.0), 0.1)):
+        w[o_ws + 4] = bs
+        info = {}
+        res[(bs > 0, wd)] = O.tensor_step(p, g, O.init_state(5, 4, C), w, C, 3, 0.7, wd, out=info)
+        assert info["lam"] == pytest.approx(math.exp(bs), rel=1e-14)
+    d1, d2 = p - res[(False, 0.0)], p - res[(True, 0.0)]
+    np.testing.assert_allclose(d2, 2.0 * d1, rtol=1e-12)
+    e1, e2 = p - res[(False, 0.1)], p - res[(True, 0.1)]
+    np.testing.assert_allclose(e1 - d1, 0.7 * 0.1 * p, rtol=1e-9, atol=1e-18)   # decay term: lr * wd * p, not scaled by lam
+    np.testing.assert_allclose(e2 - d2, 0.7 * 0.1 * p, rtol=1e-9, atol=1e-18)
 
 
 # ------------------------------------------------------------------ chunked evaluation
@@ -489,7 +658,7 @@ def test_row_slab_evaluation_equals_whole_tensor(kind):
         w = rng.standard_normal(39 * 4 + 4 + 16 + 4 + 8 + 2) * 0.3
     else:
         n_theta = 29 * 4 + 4 + 16 + 4 + 8 + 2
-        w = rng.standard_normal(45 * 20 + 5 * 20 + 20 + 5 * 3 + 3 + 3 * n_theta) * 0.3
+        w = rng.standard_normal(velo_size(4, 5, 3)) * 0.3
     p0 = rng.standard_normal((m, n)) * 0.02
     gs = [rng.standard_normal((m, n)) * 1e-2 for _ in range(3)]
     res = []

@@ -249,28 +249,34 @@ def small_fc_weights(seed: int, hidden: int = 32) -> np.ndarray:
 
 
 VELO_N_STAT = 29
-VELO_LSTM_IN = VELO_N_STAT + N_TIME + 5
+N_LOSS = 3
+VELO_LSTM_IN = VELO_N_STAT + N_TIME + 5 + N_LOSS
 
 
 def velo_weight_sizes(hidden: int, lstm_hidden: int, n_bank: int):
     theta = mlp_theta_size(VELO_N_STAT, hidden)
     return {
         "Wx": (VELO_LSTM_IN, 4 * lstm_hidden), "Wh": (lstm_hidden, 4 * lstm_hidden),
-        "b": (4 * lstm_hidden,), "Wa": (lstm_hidden, n_bank), "ba": (n_bank,),
+        "Wg": (lstm_hidden, 4 * lstm_hidden), "b": (4 * lstm_hidden,),
+        "Wa": (lstm_hidden, n_bank), "ba": (n_bank,), "ws": (lstm_hidden,), "bs": (1,),
         "B": (n_bank, theta),
     }
 
 
 def velo_weights(seed: int, hidden: int = 4, lstm_hidden: int = 512, n_bank: int = 256) -> np.ndarray:
     """Seeded random hypernetwork weights, flat float32 in the order
-    Wx | Wh | b | Wa | ba | B (all row-major)."""
+    Wx | Wh | Wg | b | Wa | ba | ws | bs | B (all row-major)."""
     r = np.random.default_rng(np.random.SeedSequence([BASE_SEED, _STREAM_WEIGHTS, 1000 + seed]))
     sz = velo_weight_sizes(hidden, lstm_hidden, n_bank)
     k = 1.0 / math.sqrt(lstm_hidden)
     out = []
-    for nm in ("Wx", "Wh", "b", "Wa", "ba"):
+    for nm in ("Wx", "Wh", "Wg", "b", "Wa", "ba"):
         out.append(r.uniform(-k, k, size=sz[nm]).astype(np.float32).ravel())
-    # bank scaled so that the mixed weights have Glorot-like magnitude
-    lim = 4.0 / math.sqrt(n_bank)
+    # step-size head: wide enough that the per-tensor multiplier exp(h . ws + bs) spans about 0.5 .. 2
+    out.append(r.uniform(-4 * k, 4 * k, size=sz["ws"]).astype(np.float32).ravel())
+    out.append(r.uniform(-0.3, 0.3, size=sz["bs"]).astype(np.float32).ravel())
+    # bank scaled so that the mixed per-tensor MLP produces updates of a size comparable to the parameters
+    # (a few per cent to a few tens of per cent of rms(p) per step), like the small_fc_lopt test weights do
+    lim = 12.0 / math.sqrt(n_bank)
     out.append(r.uniform(-lim, lim, size=sz["B"]).astype(np.float32).ravel())
     return np.concatenate(out)
