@@ -73,9 +73,12 @@ typedef enum { LOPT_SMALL_FC = 0, LOPT_VELO = 1 } lopt_kind;
  * 28 + clipped gradient = 29 (VeLO, table row "Total"). */
 #define LOPT_D_SMALL_FC 39
 #define LOPT_D_VELO 29
+/* Loss features of VeLO's hypernetwork: tanh(psi/x), psi = sign(loss) ln(1 + |loss|), x in {1, 3, 10}
+ * (the paper's artifact appendix, "Basic Usage": the current loss value is passed to VeLO's step). */
+#define LOPT_N_LOSS 3
 /* Width of the VeLO hypernetwork's LSTM input: 29 log-statistics + 11 time features
- * + one-hot of min(ndim, 4). */
-#define LOPT_VELO_LSTM_IN 45
+ * + one-hot of min(ndim, 4) + 3 loss features. */
+#define LOPT_VELO_LSTM_IN 48
 
 typedef struct {
   uint32_t struct_size; /* = sizeof(lopt_config) */
@@ -107,8 +110,9 @@ lopt_status lopt_default_config(uint32_t kind, lopt_config* cfg);
  * configuration is invalid.
  *   small_fc_lopt: W1[39,H] b1[H] W2[H,H] b2[H] W3[H,2] b3[2]            (row-major; MLP of the
  *                  pseudocode of Kernel 2: Linear1, ReLU, Linear2, ReLU, Linear3)
- *   VeLO:          Wx[45,4H_L] Wh[H_L,4H_L] b[4H_L] Wa[H_L,K] ba[K] B[K,P] with
- *                  P = 29H + H + H*H + H + 2H + 2; gate order i,f,g,o; row q of B is a
+ *   VeLO:          Wx[48,4H_L] Wh[H_L,4H_L] Wg[H_L,4H_L] b[4H_L] Wa[H_L,K] ba[K] ws[H_L] bs[1] B[K,P]
+ *                  with P = 29H + H + H*H + H + 2H + 2; gate order i,f,g,o; Wg multiplies the
+ *                  cross-tensor input, (ws, bs) is the step-size head; row q of B is a
  *                  flattened per-element MLP in the small_fc_lopt order with 29 inputs. */
 size_t lopt_weights_count(const lopt_config* cfg);
 
@@ -151,10 +155,13 @@ lopt_status lopt_init_state(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* des
  *   1. M_i <- beta_i M_i + (1-beta_i) g;  V <- beta_4 V + (1-beta_4) g^2;
  *      r_k <- beta r_k + (1-beta) row_mean(g^2);  c_k <- beta c_k + (1-beta) col_mean(g^2)
  *   2. per tensor and feature f: s_f = mean over the tensor of feature_f^2
- *   3. (VeLO) one LSTM-cell step per tensor on [0.05 ln(s_f + 1e-30), tanh(step/x), one-hot(ndim)],
- *      per-tensor MLP weights theta = (h W_a + b_a) B
+ *   3. (VeLO) one LSTM-cell step per tensor on u = [0.05 ln(s_f + 1e-30), tanh(step/x), one-hot(ndim),
+ *      loss features]: gates z = u Wx + h Wh + hbar Wg + b, where hbar is the mean over the tensors of
+ *      THIS call's list of their LSTM outputs h before the step (zero state: zeros); per-tensor MLP
+ *      weights theta = (h' W_a + b_a) B and step-size multiplier lam = exp(h' . ws + bs)
+ *      (small_fc_lopt: lam = 1)
  *   4. per element: x_f = feature_f / sqrt(s_f + eps_norm) (time features un-normalized),
- *      (direction, magnitude) = MLP(x), delta = direction * exp(alpha*magnitude) * beta,
+ *      (direction, magnitude) = MLP(x), delta = lam * direction * exp(alpha*magnitude) * beta,
  *      p <- p - lr * (delta + weight_decay * p)
  * params_host, grads_host, state_host: host arrays of n device pointers (grads are read only).
  * step: number of updates already applied (0 on the first call), must be >= 0.
@@ -164,6 +171,12 @@ lopt_status lopt_step(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* descs_hos
                       float* const* params_host, const float* const* grads_host,
                       void* const* state_host, void* workspace, int64_t step, float lr,
                       float weight_decay, void* hip_stream);
+
+/* The loss value that goes with the gradients of the following steps (the paper's VeLO usage passes the
+ * current loss to Optimizer.step; artifact appendix, "Basic Usage"). Host scalar, finite; used by every
+ * lopt_step / lopt_step_static through this context until set again; 0 (no loss features) when never
+ * set. small_fc_lopt ignores it. Errors: LOPT_EINVAL (null ctx, non-finite loss). */
+lopt_status lopt_set_loss(lopt_ctx* ctx, float loss);
 
 /* lopt_step for callers that cannot allocate device memory: code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc. Same arguments, semantics and results as lopt_step, minus the

@@ -16,7 +16,8 @@ _STATUS = {0: "LOPT_OK", 1: "LOPT_EINVAL", 2: "LOPT_ESHAPE", 3: "LOPT_ESTATE", 4
 STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = ["lopt_default_config", "lopt_weights_count", "lopt_create", "lopt_destroy", "lopt_state_bytes",
-           "lopt_init_state", "lopt_step", "lopt_step_static", "lopt_stats_offsets", "lopt_last_error",
+           "lopt_init_state", "lopt_step", "lopt_step_static", "lopt_set_loss", "lopt_stats_offsets",
+           "lopt_last_error",
            "lopt_profile_enable", "lopt_profile_read", "lopt_pass_name"]
 
 
@@ -71,6 +72,8 @@ def lib() -> C.CDLL:
     L.lopt_step_static.argtypes = [vp, sz, C.POINTER(lopt_tensor_desc), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
                                    C.c_int64, C.c_float, C.c_float, vp]
     L.lopt_step_static.restype = C.c_int
+    L.lopt_set_loss.argtypes = [vp, C.c_float]
+    L.lopt_set_loss.restype = C.c_int
     L.lopt_stats_offsets.argtypes = [vp, sz, C.POINTER(lopt_tensor_desc), C.POINTER(sz)]
     L.lopt_stats_offsets.restype = C.c_int
     L.lopt_profile_enable.argtypes = [vp, C.c_int]
@@ -144,19 +147,34 @@ class LearnedOptimizer:
                                          C.c_void_p(self.workspace.data_ptr()), self._stream()), self._ctx)
         self.step_count = 0
 
+    def set_loss(self, loss: float):
+        """The loss value that goes with the gradients of the following steps (VeLO's loss features)."""
+        _check(lib().lopt_set_loss(self._ctx, float(loss)), self._ctx)
+
     def step(self, params: List, grads: List, lr: float = 1.0, weight_decay: float = 0.0,
-             step: Optional[int] = None, static: bool = False):
-        """lopt_step, or lopt_step_static (library-owned fixed scratch, no allocation) with static=True."""
-        assert len(params) == self.n and len(grads) == self.n
-        pp = (C.c_void_p * max(self.n, 1))(*[p.data_ptr() for p in params])
-        gp = (C.c_void_p * max(self.n, 1))(*[g.data_ptr() for g in grads])
+             step: Optional[int] = None, static: bool = False, loss: Optional[float] = None,
+             indices: Optional[Sequence[int]] = None):
+        """lopt_step, or lopt_step_static (library-owned fixed scratch, no allocation) with static=True.
+        `loss`, if given, is handed to lopt_set_loss first. `indices` steps only those tensors of the list this
+        object was built for (params/grads then hold just them, in that order); the others keep their state."""
+        if indices is None:
+            n, descs, sp = self.n, self._descs, self._state_ptrs
+        else:
+            n = len(indices)
+            descs = (lopt_tensor_desc * max(n, 1))(*[self._descs[i] for i in indices])
+            sp = (C.c_void_p * max(n, 1))(*[self.state[i].data_ptr() for i in indices])
+        assert len(params) == n and len(grads) == n
+        if loss is not None:
+            self.set_loss(loss)
+        pp = (C.c_void_p * max(n, 1))(*[p.data_ptr() for p in params])
+        gp = (C.c_void_p * max(n, 1))(*[g.data_ptr() for g in grads])
         t = self.step_count if step is None else step
         with self._torch.cuda.device(self.device):
             if static:
-                _check(lib().lopt_step_static(self._ctx, self.n, self._descs, pp, gp, self._state_ptrs, t, lr,
+                _check(lib().lopt_step_static(self._ctx, n, descs, pp, gp, sp, t, lr,
                                               weight_decay, self._stream()), self._ctx)
             else:
-                _check(lib().lopt_step(self._ctx, self.n, self._descs, pp, gp, self._state_ptrs,
+                _check(lib().lopt_step(self._ctx, n, descs, pp, gp, sp,
                                        C.c_void_p(self.workspace.data_ptr()), t, lr, weight_decay,
                                        self._stream()), self._ctx)
         self.step_count = t + 1

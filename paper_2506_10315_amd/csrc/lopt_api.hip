@@ -86,6 +86,7 @@ struct Plan {
   uint64_t total_elems = 0;
   std::vector<size_t> state_bytes;
   uint64_t oLstmU = 0, oHNew = 0;   // VeLO scratch (floats)
+  uint64_t oHbarPart = 0, oBeff = 0; // VeLO cross-tensor term: slice sums of h, gate bias with the term added
   uint64_t oCounters = 0;           // kMaxGroups ints: tile counters of the strip-form apply kernel
   uint64_t ws_floats = 0;
 };
@@ -105,6 +106,7 @@ struct lopt_ctx {
   Plan plan;
   bool plan_valid = false;
   TableStore heap, fixed;
+  float loss = 0.f;                // lopt_set_loss: goes with the gradients of the following steps (VeLO)
   uint64_t id = 0;                 // names this context as the owner of the static scratch's contents
   void* static_scratch = nullptr;  // device address of `scratch` on ctx->device
   void* h_stage = nullptr;         // pinned staging
@@ -195,6 +197,8 @@ void build_plan(const lopt_ctx* ctx, size_t n, const lopt_tensor_desc* d, Plan* 
   if (velo) {
     pl->oLstmU = take((uint64_t)n * kLstmInPad);
     pl->oHNew = take((uint64_t)n * ctx->cfg.lstm_hidden);
+    pl->oHbarPart = take((uint64_t)kMixSlices * ctx->cfg.lstm_hidden);
+    pl->oBeff = take(4ull * ctx->cfg.lstm_hidden);
   }
   // Apply tiles get shorter towards the end of every tensor group of the pipeline (a single group if it is off): the
   // strip apply kernel hands tiles out in table order, so the last tiles of a launch decide how long the chip idles
@@ -376,6 +380,7 @@ StepArgs make_args(const lopt_ctx* ctx, int64_t step, float lr, float wd, int n_
   A.kind = (int)c.kind; A.H = (int)c.hidden; A.HP = ctx->HP; A.F = ctx->F;
   A.HL = (int)c.lstm_hidden; A.K = (int)c.n_bank; A.P = ctx->P;
   A.n_tensors = n_tensors;
+  A.loss = ctx->loss;
   return A;
 }
 
@@ -406,7 +411,7 @@ size_t lopt_weights_count(const lopt_config* c) {
   if (!config_ok(c, nullptr)) return 0;
   if (c->kind == LOPT_SMALL_FC) return mlp_count(LOPT_D_SMALL_FC, (int)c->hidden);
   const size_t HL = c->lstm_hidden, K = c->n_bank, P = mlp_count(LOPT_D_VELO, (int)c->hidden);
-  return (size_t)LOPT_VELO_LSTM_IN * 4 * HL + HL * 4 * HL + 4 * HL + HL * K + K + K * P;
+  return (size_t)LOPT_VELO_LSTM_IN * 4 * HL + 2 * (HL * 4 * HL) + 4 * HL + HL * K + K + HL + 1 + K * P;
 }
 
 lopt_status lopt_create(const lopt_config* cfg, const float* weights_host, size_t n_weights, lopt_ctx** out) {
@@ -502,9 +507,12 @@ lopt_status lopt_create(const lopt_config* cfg, const float* weights_host, size_
     const float* w = ctx->d_weights;
     ctx->W.Wx = w; w += (size_t)LOPT_VELO_LSTM_IN * 4 * HL;
     ctx->W.Wh = w; w += HL * 4 * HL;
+    ctx->W.Wg = w; w += HL * 4 * HL;
     ctx->W.b = w; w += 4 * HL;
     ctx->W.Wa = w; w += HL * K;
     ctx->W.ba = w; w += K;
+    ctx->W.ws = w; w += HL;
+    ctx->W.bs = w; w += 1;
     ctx->W.B = w;
   }
 #undef CREATE_TRY
@@ -697,7 +705,7 @@ static lopt_status step_impl(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* de
       launch_accum_stats(S, A, s);
       launch_finalize(S, A, ctx->W, ws + pl.oLstmU, s);
       if (velo) {
-        launch_velo_lstm(S, A, ctx->W, ws + pl.oLstmU, ws + pl.oHNew, s);
+        launch_velo_lstm(S, A, ctx->W, ws + pl.oLstmU, ws + pl.oBeff, ws + pl.oHNew, s);
         launch_velo_head(S, A, ctx->W, ws + pl.oHNew, s);
       }
     };
@@ -705,6 +713,8 @@ static lopt_status step_impl(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* de
     // the row/column pass reads only the gradients (4 of the step's 72 bytes per element): whole list, up front
     launch_rowcol_sums(L, A, stream);
     launch_rc_update(L, A, stream);
+    // the cross-tensor term reads every tensor's LSTM output of the previous step: before any group rewrites its own
+    if (velo) launch_velo_mix(L, A, ctx->W, ws + pl.oHbarPart, ws + pl.oBeff, stream);
     HIP_TRY(ctx, hipEventRecord(ctx->ev_fork, stream));       // aux joins the caller's stream here ...
     HIP_TRY(ctx, hipStreamWaitEvent(aux, ctx->ev_fork, 0));
     stats_passes(sub(0), stream);
@@ -744,7 +754,8 @@ static lopt_status step_impl(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* de
   launch_finalize(L, A, ctx->W, ws + pl.oLstmU, stream);
   MARK(4);
   if (ctx->cfg.kind == LOPT_VELO) {
-    launch_velo_lstm(L, A, ctx->W, ws + pl.oLstmU, ws + pl.oHNew, stream);
+    launch_velo_mix(L, A, ctx->W, ws + pl.oHbarPart, ws + pl.oBeff, stream);
+    launch_velo_lstm(L, A, ctx->W, ws + pl.oLstmU, ws + pl.oBeff, ws + pl.oHNew, stream);
     MARK(5);
     launch_velo_head(L, A, ctx->W, ws + pl.oHNew, stream);
     MARK(6);
@@ -771,6 +782,13 @@ lopt_status lopt_step_static(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* de
                              const float* const* grads, void* const* state, int64_t step, float lr,
                              float weight_decay, void* hip_stream) {
   return step_impl(ctx, n, descs, params, grads, state, nullptr, step, lr, weight_decay, hip_stream, true);
+}
+
+lopt_status lopt_set_loss(lopt_ctx* ctx, float loss) {
+  if (!ctx) return fail(nullptr, LOPT_EINVAL, "ctx is null");
+  if (!std::isfinite(loss)) return fail(ctx, LOPT_EINVAL, "loss must be finite");
+  ctx->loss = loss;
+  return LOPT_OK;
 }
 
 lopt_status lopt_profile_enable(lopt_ctx* ctx, int on) {

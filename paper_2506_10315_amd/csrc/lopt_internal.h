@@ -19,7 +19,8 @@ constexpr int kStatStride = 20;   // floats per tile in the per-tile statistics 
 constexpr int kRcStride = 12;     // floats per block in the row/column partials (9 used)
 constexpr int kNStat = 17;        // per-element statistics accumulated per tile
 constexpr int kStatsPerTensor = 32;
-constexpr int kLstmInPad = 48;    // LOPT_VELO_LSTM_IN rounded up
+constexpr int kLstmInPad = 48;    // LOPT_VELO_LSTM_IN rounded up to a multiple of 4
+constexpr int kMixSlices = 64;    // at most this many slices of the tensor list in the cross-tensor mean
 #ifndef LOPT_APPLY_ROWS
 #define LOPT_APPLY_ROWS 128
 #endif
@@ -64,6 +65,7 @@ struct StepArgs {
   int kind, H, HP, F;         // F = number of normalized per-element features (28 or 29)
   int HL, K, P;               // VeLO: LSTM width, bank rows, floats per per-tensor MLP
   int n_tensors;
+  float loss;                 // VeLO: loss value that goes with this step's gradients
 };
 
 // Device weights of the optimizer, owned by the context.
@@ -72,7 +74,8 @@ struct WeightsDev {
   const float* mlp;    // W1[39,H] b1[H] W2[H,H] b2[H] W3[H,2] b3[2]
   const float* mlp_tail;  // W2[HP,HP] b2[HP] W3[HP,2] b3[2] pad[2] W1[28,HP]: zero-padded to the padded width HP
   // VeLO
-  const float* Wx; const float* Wh; const float* b; const float* Wa; const float* ba; const float* B;
+  const float* Wx; const float* Wh; const float* Wg; const float* b; const float* Wa; const float* ba;
+  const float* ws; const float* bs; const float* B;
 };
 
 struct Launch {
@@ -94,7 +97,10 @@ void launch_rowcol_sums(const Launch&, const StepArgs&, hipStream_t);
 void launch_rc_update(const Launch&, const StepArgs&, hipStream_t);
 void launch_accum_stats(const Launch&, const StepArgs&, hipStream_t);
 void launch_finalize(const Launch&, const StepArgs&, const WeightsDev&, float* lstm_u, hipStream_t);
-void launch_velo_lstm(const Launch&, const StepArgs&, const WeightsDev&, const float* lstm_u,
+// cross-tensor term over the WHOLE list: hbar = mean of the tensors' h, b_eff = b + hbar Wg (must run before any
+// tensor's LSTM state is rewritten)
+void launch_velo_mix(const Launch&, const StepArgs&, const WeightsDev&, float* hbar_part, float* b_eff, hipStream_t);
+void launch_velo_lstm(const Launch&, const StepArgs&, const WeightsDev&, const float* lstm_u, const float* b_eff,
                       float* h_new, hipStream_t);
 void launch_velo_head(const Launch&, const StepArgs&, const WeightsDev&, const float* h_new,
                       hipStream_t);

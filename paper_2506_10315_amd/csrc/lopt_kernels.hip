@@ -376,7 +376,7 @@ __global__ void __launch_bounds__(kBlock) k_finalize(const TensorDev* __restrict
                                                      int* __restrict__ apply_counter) {
   __shared__ double part[8][32];
   __shared__ double tot[48];
-  __shared__ float s_stats[32], s_scale[32], s_tfeat[LOPT_N_TIME];
+  __shared__ float s_stats[32], s_scale[32], s_tfeat[LOPT_N_TIME], s_lfeat[LOPT_N_LOSS];
   const int ti = tensor0 + (int)blockIdx.x;
   const TensorDev& T = tensors[ti];
   if (blockIdx.x == 0 && threadIdx.x == 0) *apply_counter = 0;   // the apply pass of this sub-list starts at its first tile
@@ -384,6 +384,13 @@ __global__ void __launch_bounds__(kBlock) k_finalize(const TensorDev* __restrict
     // time features tanh(t/x) (feature table of small_fc_lopt, row "Time Features")
     const double xs[LOPT_N_TIME] = {1, 3, 10, 30, 100, 300, 1000, 3000, 1e4, 3e4, 1e5};
     s_tfeat[threadIdx.x - 64] = (float)tanh((double)A.step / xs[threadIdx.x - 64]);
+  }
+  if (threadIdx.x >= 96 && threadIdx.x < 96 + LOPT_N_LOSS) {
+    // loss features tanh(psi / x), psi = sign(loss) ln(1 + |loss|) (the loss value VeLO's step is given)
+    const double xs[LOPT_N_LOSS] = {1, 3, 10};
+    const double l = (double)A.loss;
+    const double psi = copysign(log1p(fabs(l)), l);
+    s_lfeat[threadIdx.x - 96] = (float)tanh(psi / xs[threadIdx.x - 96]);
   }
   const int q = threadIdx.x & 31, seg = threadIdx.x >> 5;
   const int ntiles = T.nrt * T.nct;
@@ -461,15 +468,16 @@ __global__ void __launch_bounds__(kBlock) k_finalize(const TensorDev* __restrict
       prep[LOPT_N_ELEM_FEATS * HP + u] = b;
     }
   } else {
-    // LSTM input: 0.05*ln(s_f + 1e-30), time features, one-hot of min(ndim, 4)
+    // LSTM input: 0.05*ln(s_f + 1e-30), time features, one-hot of min(ndim, 4), loss features
     float* u = lstm_u + (size_t)ti * kLstmInPad;
     const int t = threadIdx.x;
     if (t < LOPT_D_VELO) u[t] = 0.05f * logf(s_stats[t] + 1e-30f);
     else if (t < LOPT_D_VELO + LOPT_N_TIME) u[t] = s_tfeat[t - LOPT_D_VELO];
-    else if (t < LOPT_VELO_LSTM_IN) {
+    else if (t < LOPT_D_VELO + LOPT_N_TIME + 5) {
       const int nd = T.ndim < 4u ? (int)T.ndim : 4;
       u[t] = (t - (LOPT_D_VELO + LOPT_N_TIME)) == nd ? 1.f : 0.f;
-    } else if (t < kLstmInPad) u[t] = 0.f;
+    } else if (t < LOPT_VELO_LSTM_IN) u[t] = s_lfeat[t - (LOPT_D_VELO + LOPT_N_TIME + 5)];
+    else if (t < kLstmInPad) u[t] = 0.f;
   }
 }
 
@@ -477,6 +485,63 @@ void launch_finalize(const Launch& L, const StepArgs& A, const WeightsDev& W, fl
   if (L.n_tensors == 0) return;
   hipLaunchKernelGGL(k_finalize, dim3(L.n_tensors), dim3(kBlock), 0, s, L.tensors, L.ws, A, W, lstm_u, L.tensor0,
                      L.apply_counter);
+}
+
+// ----------------------------------------------------------------------------- VeLO cross-tensor term
+
+// hbar = mean over the tensors of the list of their LSTM outputs h (as left by the previous step), in two stages with
+// a fixed order: slice s of the list -> part[s][j] (this kernel: lane = unit j, the four wavefronts take every fourth
+// tensor of the slice and meet in LDS), then the slices in index order (k_velo_mixbias).
+__global__ void __launch_bounds__(kBlock) k_velo_hbar(const TensorDev* __restrict__ tensors, int n_tensors, int per_slice,
+                                                      int HL, float* __restrict__ part) {
+  __shared__ float red[4][kWave];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j = blockIdx.x * kWave + lane;
+  const int t0 = blockIdx.y * per_slice, t1 = min(t0 + per_slice, n_tensors);
+  float a = 0.f;
+  if (j < HL)
+    for (int t = t0 + wave; t < t1; t += 4) {
+      const TensorDev& T = tensors[t];
+      a += T.st[4 * (size_t)T.padN + 3 * (size_t)T.padm + 3 * (size_t)T.padn + j];
+    }
+  red[wave][lane] = a;
+  __syncthreads();
+  if (wave == 0 && j < HL) part[(size_t)blockIdx.y * HL + j] = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
+}
+
+// b_eff[col] = b[col] + sum_j hbar[j] Wg[j][col]: the cross-tensor input is the same for every tensor of the list, so
+// its gate contribution is computed once and takes the place of the LSTM bias.
+__global__ void __launch_bounds__(kBlock) k_velo_mixbias(const float* __restrict__ part, int n_slices, int n_tensors, int HL,
+                                                         WeightsDev W, float* __restrict__ b_eff) {
+  __shared__ float hbar[1024];
+  for (int j = threadIdx.x; j < HL; j += kBlock) {
+    double a = 0.0;
+    for (int s = 0; s < n_slices; ++s) a += (double)part[(size_t)s * HL + j];
+    hbar[j] = (float)(a / (double)n_tensors);
+  }
+  __syncthreads();
+  const int col = blockIdx.x * kBlock + threadIdx.x, G = 4 * HL;
+  if (col >= G) return;
+  float a0 = 0.f, a1 = 0.f;
+  int j = 0;
+  for (; j + 1 < HL; j += 2) {
+    a0 += hbar[j] * W.Wg[(size_t)j * G + col];
+    a1 += hbar[j + 1] * W.Wg[(size_t)(j + 1) * G + col];
+  }
+  if (j < HL) a0 += hbar[j] * W.Wg[(size_t)j * G + col];
+  b_eff[col] = W.b[col] + (a0 + a1);
+}
+
+void launch_velo_mix(const Launch& L, const StepArgs& A, const WeightsDev& W, float* hbar_part, float* b_eff, hipStream_t s) {
+  if (L.n_tensors == 0) return;
+  int n_slices = (L.n_tensors + 31) / 32;
+  if (n_slices > kMixSlices) n_slices = kMixSlices;
+  const int per_slice = (L.n_tensors + n_slices - 1) / n_slices;
+  n_slices = (L.n_tensors + per_slice - 1) / per_slice;
+  hipLaunchKernelGGL(k_velo_hbar, dim3((A.HL + kWave - 1) / kWave, n_slices), dim3(kBlock), 0, s, L.tensors, L.n_tensors,
+                     per_slice, A.HL, hbar_part);
+  hipLaunchKernelGGL(k_velo_mixbias, dim3((4 * A.HL + kBlock - 1) / kBlock), dim3(kBlock), 0, s, hbar_part, n_slices,
+                     L.n_tensors, A.HL, W, b_eff);
 }
 
 // ----------------------------------------------------------------------------- VeLO hypernetwork
@@ -496,7 +561,8 @@ constexpr int kLstmPairsPerTrip = 16;
 typedef float f32x16_l __attribute__((ext_vector_type(16)));
 
 __global__ void __launch_bounds__(kBlock) k_velo_lstm(const TensorDev* __restrict__ tensors, StepArgs A, WeightsDev W,
-                                                      const float* __restrict__ lstm_u, float* __restrict__ h_new) {
+                                                      const float* __restrict__ lstm_u, const float* __restrict__ b_eff,
+                                                      float* __restrict__ h_new) {
   __shared__ float part[4][2][32][32];   // [wavefront][column tile][tensor][column]: 32 KB
   const int HL = A.HL, G = 4 * HL;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -562,7 +628,7 @@ __global__ void __launch_bounds__(kBlock) k_velo_lstm(const TensorDev* __restric
 #pragma unroll
           for (int g2 = 0; g2 < 4; ++g2) {
             const int c = g2 * 8 + uu;
-            zz[g2] = W.b[g2 * HL + unit] + ((part[0][tile][tt][c] + part[1][tile][tt][c]) + (part[2][tile][tt][c] + part[3][tile][tt][c]));
+            zz[g2] = b_eff[g2 * HL + unit] + ((part[0][tile][tt][c] + part[1][tile][tt][c]) + (part[2][tile][tt][c] + part[3][tile][tt][c]));
           }
           const float ig = 1.f / (1.f + expf(-zz[0]));
           const float fg = 1.f / (1.f + expf(-zz[1]));
@@ -577,15 +643,15 @@ __global__ void __launch_bounds__(kBlock) k_velo_lstm(const TensorDev* __restric
   }
 }
 
-void launch_velo_lstm(const Launch& L, const StepArgs& A, const WeightsDev& W, const float* lstm_u, float* h_new,
-                      hipStream_t s) {
+void launch_velo_lstm(const Launch& L, const StepArgs& A, const WeightsDev& W, const float* lstm_u, const float* b_eff,
+                      float* h_new, hipStream_t s) {
   if (L.n_tensors == 0) return;
   dim3 grid((L.n_tensors + kLstmTensors - 1) / kLstmTensors, (A.HL + kLstmUnits - 1) / kLstmUnits);
   // a sub-list starts at tensor L.tensor0: the kernel indexes tensors, inputs and outputs from there
   StepArgs As = A;
   As.n_tensors = L.n_tensors;
   hipLaunchKernelGGL(k_velo_lstm, grid, dim3(kBlock), 0, s, L.tensors + L.tensor0, As, W,
-                     lstm_u + (size_t)L.tensor0 * kLstmInPad, h_new + (size_t)L.tensor0 * A.HL);
+                     lstm_u + (size_t)L.tensor0 * kLstmInPad, b_eff, h_new + (size_t)L.tensor0 * A.HL);
 }
 
 // Partial matrix-vector product for the hypernetwork head: out[w][c0 + 64 c + lane] = sum over rows
@@ -622,12 +688,15 @@ __device__ __forceinline__ void matvec4(const float* __restrict__ x, int n_in, c
 }
 
 // Head of the hypernetwork for one tensor: alpha = h W_a + b_a, theta = alpha B, written as the
-// prepared (zero-padded, first layer scaled) per-tensor MLP. Also stores the new h into the state.
+// prepared (zero-padded, first layer scaled) per-tensor MLP; the step-size multiplier lam = exp(h . ws + bs)
+// is folded into the direction column of the last layer (W3[:, 0], b3[0]), so the apply pass does not see it.
+// Also stores the new h into the state.
 // Both products split their reduction across the workgroup's wavefronts (combined through LDS in a
 // fixed order); lanes own output columns, so weight reads are coalesced.
 __global__ void __launch_bounds__(1024) k_velo_head(const TensorDev* __restrict__ tensors, float* __restrict__ ws,
                                                       StepArgs A, WeightsDev W, const float* __restrict__ h_new) {
   extern __shared__ float sh[];  // h[HL] | alpha[K] | part[nw][max(K, P) rounded up to 64]
+  __shared__ float s_lam;
   const TensorDev& T = tensors[blockIdx.x];
   const int HL = A.HL, K = A.K, H = A.H, HP = A.HP, F = LOPT_D_VELO, P = A.P;
   const int W64 = ((K > P ? K : P) + 63) & ~63;
@@ -646,6 +715,12 @@ __global__ void __launch_bounds__(1024) k_velo_head(const TensorDev* __restrict_
   const int prep_n = (F + 1) * HP + HP * HP + HP + 2 * HP + 2;
   for (int i = threadIdx.x; i < prep_n; i += blockDim.x) prep[i] = 0.f;
   __syncthreads();
+  if (wave == 0) {
+    float a = 0.f;
+    for (int i = lane; i < HL; i += kWave) a += sh_h[i] * W.ws[i];
+    a = wave_sum(a);
+    if (lane == 0) s_lam = expf(a + W.bs[0]);
+  }
   // alpha = h W_a: wavefront w reduces rows w, w+nw, ...; a lane owns four output columns 64 apart
   for (int q0 = 0; q0 < K; q0 += 256) matvec4(sh_h, HL, W.Wa, K, q0, wave, nw, lane, part, W64);
   __syncthreads();
@@ -669,8 +744,8 @@ __global__ void __launch_bounds__(1024) k_velo_head(const TensorDev* __restrict_
     else if ((o -= F * H) < H) dst = F * HP + o;
     else if ((o -= H) < H * H) { const int a = o / H, u = o - a * H; dst = (F + 1) * HP + a * HP + u; }
     else if ((o -= H * H) < H) dst = (F + 1) * HP + HP * HP + o;
-    else if ((o -= H) < 2 * H) dst = (F + 1) * HP + HP * HP + HP + o;
-    else { o -= 2 * H; dst = (F + 1) * HP + HP * HP + HP + 2 * HP + o; }
+    else if ((o -= H) < 2 * H) { dst = (F + 1) * HP + HP * HP + HP + o; if (!(o & 1)) th *= s_lam; }   // W3[a][0]: direction
+    else { o -= 2 * H; dst = (F + 1) * HP + HP * HP + HP + 2 * HP + o; if (o == 0) th *= s_lam; }       // b3[0]
     prep[dst] = th;
   }
 }

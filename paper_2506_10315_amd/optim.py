@@ -35,29 +35,36 @@ class LearnedOptTorch(torch.optim.Optimizer):
                     raise ValueError("parameters must be contiguous fp32 CUDA tensors")
             dev = ps[0].device if ps else torch.device("cuda:0")
             self._engines.append(LearnedOptimizer(self._cfg, weights, [tuple(p.shape) or (1,) for p in ps], device=dev))
-        self._zero_grads = {}
 
     @torch.no_grad()
-    def step(self, closure=None, loss=None):
-        """One optimizer step. `loss` is accepted for interface compatibility with the paper's VeLO usage
-        (`optimizer.step(loss)`); this implementation's VeLO hypernetwork has no loss feature."""
+    def step(self, loss=None, closure=None):
+        """One optimizer step. `loss` (a Python number or a one-element tensor) is the current loss value, the paper's
+        call form `optimizer.step(loss)` for VeLO: it feeds the loss features of VeLO's hypernetwork
+        (lopt_set_loss); small_fc_lopt ignores it. A callable in its place is taken as torch's closure. Without it (and without a closure's return value) the loss
+        features are those of a zero loss. Parameters whose .grad is None are skipped, as torch optimizers do:
+        neither they nor their accumulators move, and they do not count in VeLO's cross-tensor mean of that step."""
         out = None
+        if callable(loss) and closure is None:
+            loss, closure = None, loss
         if closure is not None:
             with torch.enable_grad():
                 out = closure()
+        if loss is None:
+            loss = out
+        loss_value = 0.0 if loss is None else float(loss)
         for group, eng in zip(self.param_groups, self._engines):
             ps = group["params"]
+            idx = [i for i, p in enumerate(ps) if p.grad is not None]
+            if not idx:
+                continue
             gs = []
-            for p in ps:
-                g = p.grad
-                if g is None:
-                    g = self._zero_grads.get(p)
-                    if g is None:
-                        g = self._zero_grads[p] = torch.zeros_like(p)
-                elif not (g.is_contiguous() and g.dtype == torch.float32):
+            for i in idx:
+                g = ps[i].grad
+                if not (g.is_contiguous() and g.dtype == torch.float32):
                     g = g.contiguous().float()
                 gs.append(g)
-            eng.step(list(ps), gs, lr=float(group["lr"]), weight_decay=float(group["weight_decay"]))
+            eng.step([ps[i] for i in idx], gs, lr=float(group["lr"]), weight_decay=float(group["weight_decay"]),
+                     loss=loss_value, indices=None if len(idx) == len(ps) else idx)
         return out
 
     def state_dict(self):

@@ -44,11 +44,11 @@ def test_wrapper_matches_oracle_and_resumes(kind):
         loss.backward()
         lr = float(np.float32(opt.param_groups[0]["lr"]))
         grads = [p.grad.detach().cpu().numpy().reshape(q.shape) for p, q in zip(params, p_ora)]
-        opt.step(loss=loss)                      # the paper's call form for VeLO
+        opt.step(loss)                           # the paper's call form for VeLO: the loss value is an input
         sched.step()
+        p_ora = O.list_step(p_ora, grads, st_ora, w, ocfg, t, lr, float(np.float32(0.01)),
+                            [max(1, p.dim()) for p in params], loss=float(np.float32(loss.item())))
         for i, p in enumerate(params):
-            nd = max(1, p.dim())
-            p_ora[i] = O.tensor_step(p_ora[i], grads[i], st_ora[i], w, ocfg, t, lr, float(np.float32(0.01)), ndim=nd)
             e = O.rel_err(p.detach().cpu().numpy().reshape(p_ora[i].shape), p_ora[i])
             assert e <= Hn.TOL_PARAM, f"step {t} param {i}: {e:.2e}"
         if t == 2:
@@ -66,7 +66,7 @@ def test_wrapper_matches_oracle_and_resumes(kind):
         opt2.zero_grad()
         loss = torch.nn.functional.cross_entropy(model2(x), y)
         loss.backward()
-        opt2.step()
+        opt2.step(loss)
         sched2.step()
     for a, b in zip(final, model2.parameters()):
         assert torch.equal(a, b.detach())
@@ -76,3 +76,27 @@ def Hn_shape(p):
     from paper_2506_10315_amd.binding import flatten_shape
     _, r, c = flatten_shape(tuple(p.shape))
     return (r, c)
+
+
+def test_parameters_without_gradients_are_skipped_and_the_loss_matters_for_velo():
+    import torch
+    from paper_2506_10315_amd.optim import LearnedOptTorch
+    cfg = Hn.make_cfg("velo", lstm_hidden=32, n_bank=16)
+    w = Hn.random_weights(cfg, 8)
+    res = {}
+    for loss_value in (0.7, 9.0):
+        model = _model()
+        frozen = model[2].bias
+        opt = LearnedOptTorch(model.parameters(), w, kind="velo", lr=0.5, weight_decay=0.01, cfg=cfg)
+        before = frozen.detach().clone()
+        for t in range(3):
+            x, y = _batch(t)
+            opt.zero_grad(set_to_none=True)
+            torch.nn.functional.cross_entropy(model(x), y).backward()
+            frozen.grad = None                                  # e.g. an unused or frozen parameter
+            opt.step(loss_value)
+        torch.cuda.synchronize()
+        assert torch.equal(frozen.detach(), before)             # no update, no weight decay
+        assert bool((opt._engines[0].state[3] == 0).all())      # its accumulators never moved
+        res[loss_value] = [p.detach().clone() for p in model.parameters()]
+    assert any(not torch.equal(a, b) for a, b in zip(res[0.7], res[9.0]))   # the loss value reaches the update

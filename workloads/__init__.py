@@ -218,6 +218,13 @@ def lr_at(w: Workload, step: int) -> float:
     return float(np.float32(v))
 
 
+def loss_at(config_id: int, step: int) -> float:
+    """Synthetic training-loss value handed to the step beside the gradients (VeLO takes it): a decaying curve with a
+    ripple, float32-representable, the same for both sides of a parity test."""
+    v = 0.5 + 6.0 * math.exp(-step / 25.0) + 0.3 * math.sin(1.7 * step + 0.1 * config_id)
+    return float(np.float32(v))
+
+
 # --------------------------------------------------------------------------- optimizer weights
 
 N_TIME = 11
