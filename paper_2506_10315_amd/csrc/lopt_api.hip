@@ -76,6 +76,50 @@ struct TableStore {
   std::vector<TensorDev> last_tensors;  // what d_tensors currently holds
 };
 
+// The small_fc_lopt MLP rewritten into an equivalent one whose hidden units are rescaled by powers of two (ReLU is
+// positively homogeneous, so W1 diag(s1), b1 s1, diag(1/s1) W2 diag(s2), b2 s2, diag(1/s2) W3 computes the same
+// function; scaling by a power of two is exact in fp32). The default apply kernel carries both hidden-layer
+// contractions' operands as pairs of fp16 numbers (range 2^-24 .. 65504):
+//   s1_u makes the worst case of unit u's first-layer pre-activation, |b1_u| + sum_t |W1[28+t][u]| (time features are
+//        at most 1) + sqrt(N_max) sum_f |W1[f][u]| (a normalized feature is at most sqrt(N) in magnitude, N <= 2^31),
+//        at most 2^15: no input can make a hidden activation leave the fp16 range, and a typical activation (features
+//        of unit mean square) still sits 2^-2 .. 2^0, far above the 2^-24 grid of the low halves;
+//   s2_u puts the largest rescaled second-layer weight of output unit u between 2^12 and 2^13, so that weights many
+//        orders of magnitude below it still keep their leading bits; layer 2's result stays in fp32.
+// All apply kernels run the rewritten network (for the fp32 ones it changes nothing but exponents).
+std::vector<float> equilibrate_small_fc(const float* w, int H) {
+  const int d = LOPT_D_SMALL_FC, ne = LOPT_N_ELEM_FEATS;
+  const size_t oB1 = (size_t)d * H, oW2 = oB1 + H, oB2 = oW2 + (size_t)H * H, oW3 = oB2 + H, oB3 = oW3 + 2 * (size_t)H;
+  std::vector<float> out(w, w + oB3 + 2);
+  const double xmax = 46341.0;   // sqrt(2^31 - 1), rounded up
+  auto pow2_below = [](double target, double v) {   // largest power of two s with v * s <= target (1 if v is 0)
+    if (!(v > 0.0)) return 1.0;
+    int e = (int)std::floor(std::log2(target / v));
+    e = e < -60 ? -60 : e > 60 ? 60 : e;
+    return std::ldexp(1.0, e);
+  };
+  std::vector<double> s1(H), s2(H);
+  for (int u = 0; u < H; ++u) {
+    double b = std::fabs((double)w[oB1 + u]);
+    for (int f = 0; f < d; ++f) b += std::fabs((double)w[(size_t)f * H + u]) * (f < ne ? xmax : 1.0);
+    s1[u] = pow2_below(32768.0, b);
+  }
+  for (int u = 0; u < H; ++u) {
+    double cm = 0.0;
+    for (int a = 0; a < H; ++a) cm = std::fmax(cm, std::fabs((double)w[oW2 + (size_t)a * H + u]) / s1[a]);
+    s2[u] = pow2_below(8192.0, cm);
+  }
+  for (int u = 0; u < H; ++u) {
+    for (int f = 0; f < d; ++f) out[(size_t)f * H + u] = (float)((double)w[(size_t)f * H + u] * s1[u]);
+    out[oB1 + u] = (float)((double)w[oB1 + u] * s1[u]);
+    for (int a = 0; a < H; ++a) out[oW2 + (size_t)a * H + u] = (float)((double)w[oW2 + (size_t)a * H + u] / s1[a] * s2[u]);
+    out[oB2 + u] = (float)((double)w[oB2 + u] * s2[u]);
+    out[oW3 + 2 * (size_t)u] = (float)((double)w[oW3 + 2 * (size_t)u] / s2[u]);
+    out[oW3 + 2 * (size_t)u + 1] = (float)((double)w[oW3 + 2 * (size_t)u + 1] / s2[u]);
+  }
+  return out;
+}
+
 struct Plan {
   std::vector<lopt_tensor_desc> descs;
   std::vector<TensorDev> tensors;   // pointers filled per call
@@ -424,6 +468,13 @@ lopt_status lopt_create(const lopt_config* cfg, const float* weights_host, size_
     char buf[128];
     snprintf(buf, sizeof buf, "n_weights=%zu but this configuration needs %zu floats", n_weights, want);
     return fail(nullptr, LOPT_ESTATE, buf);
+  }
+  for (size_t i = 0; i < n_weights; ++i)
+    if (!std::isfinite(weights_host[i])) return fail(nullptr, LOPT_EINVAL, "weights_host holds a non-finite value");
+  std::vector<float> eq;
+  if (cfg->kind == LOPT_SMALL_FC) {
+    try { eq = equilibrate_small_fc(weights_host, (int)cfg->hidden); } catch (const std::bad_alloc&) { return fail(nullptr, LOPT_ENOMEM, "out of host memory"); }
+    weights_host = eq.data();   // from here on: the equivalent, rescaled network
   }
   lopt_ctx* ctx = new (std::nothrow) lopt_ctx();
   if (!ctx) return fail(nullptr, LOPT_ENOMEM, "out of host memory");

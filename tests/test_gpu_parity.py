@@ -100,6 +100,31 @@ def test_every_apply_kernel_variant_matches_the_oracle(variant, monkeypatch):
     assert worst["param"] <= Hn.TOL_PARAM
 
 
+@pytest.mark.parametrize("variant", [None, "mfma_f16x3", "mfma_f32", "valu"])
+def test_badly_scaled_weights_and_an_outlier_gradient(variant, monkeypatch):
+    # Weights that are legal but nowhere near Glorot magnitude (rows of W1 / W2 200x and 50x larger or 10^4x smaller,
+    # biases of order 10) and one gradient element 50 000 times the others in a million-element tensor: its normalized
+    # gradient feature is ~1000 and its hidden pre-activations several 10^4. The default kernel carries the MLP's
+    # operands as pairs of fp16 numbers; it must hold the same bar here as the fp32 kernels (no saturation at 65504,
+    # no loss of the small rows).
+    if variant:
+        monkeypatch.setenv("LOPT_APPLY", variant)
+    cfg = Hn.make_cfg("small_fc_lopt")
+    w = W.small_fc_weights_badly_scaled(3)
+
+    class Outlier(Hn.Case):
+        def grad(self, i, step):
+            g = super().grad(i, step)
+            if g.size > 1000:
+                g[5 % g.shape[0], 7] = 50.0
+            return g
+
+    shapes = [(1024, 1024), (64, 256), (300,), (130, 260)]
+    worst = Hn.run_free(Outlier(120, _specs(shapes)), cfg, w, 3, lr_fn=lambda t: 0.9, wd=0.01)
+    print(f"badly scaled weights, LOPT_APPLY={variant}: worst {worst}")
+    assert worst["param"] <= Hn.TOL_PARAM and worst["delta"] <= Hn.TOL_DELTA
+
+
 def test_velo_vector_alu_variant_matches_the_oracle(monkeypatch):
     monkeypatch.setenv("LOPT_APPLY", "valu")
     cfg = Hn.make_cfg("velo")

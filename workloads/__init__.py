@@ -255,6 +255,29 @@ def small_fc_weights(seed: int, hidden: int = 32) -> np.ndarray:
     return np.concatenate([p.ravel() for p in parts])
 
 
+def small_fc_weights_badly_scaled(seed: int) -> np.ndarray:
+    """Legal but far from Glorot: some input rows of the first two layers 200x / 50x larger, some 10^4x smaller, hidden
+    biases of order 10, a small last layer (so that the update stays of the order of the parameters). Hidden
+    pre-activations reach several 10^4 on an outlier element. Hidden width 32."""
+    w = small_fc_weights(seed, 32).copy()
+    H, d = 32, feature_dim("small_fc_lopt")
+    o = 0
+    W1 = w[o:o + d * H].reshape(d, H); o += d * H
+    b1 = w[o:o + H]; o += H
+    W2 = w[o:o + H * H].reshape(H, H); o += H * H
+    b2 = w[o:o + H]; o += H
+    W3 = w[o:o + 2 * H].reshape(H, 2)
+    r = np.random.default_rng(np.random.SeedSequence([BASE_SEED, _STREAM_WEIGHTS, 5000 + seed]))
+    W1[[0, 10, 3, 7]] *= np.float32(200.0)
+    W1[[5, 11, 20]] *= np.float32(1e-4)
+    W2[[2, 9]] *= np.float32(50.0)
+    W2[[4, 20]] *= np.float32(1e-4)
+    b1[:] = r.uniform(-10, 10, H).astype(np.float32)
+    b2[:] = r.uniform(-10, 10, H).astype(np.float32)
+    W3 *= np.float32(2e-4)
+    return w
+
+
 VELO_N_STAT = 29
 N_LOSS = 3
 VELO_LSTM_IN = VELO_N_STAT + N_TIME + 5 + N_LOSS
