@@ -25,9 +25,13 @@
  *    No call synchronizes the host with the device except when a cached table has to
  *    be rewritten while its previous upload is still in flight.
  *  - Every call validates its arguments on the host before launching anything and
- *    returns a status; nothing throws or aborts across this boundary. After a
- *    non-OK status, params and state are untouched and lopt_last_error() gives a
- *    message.
+ *    returns a status; nothing throws or aborts across this boundary, and
+ *    lopt_last_error() gives a message. After a status that comes from that validation
+ *    (LOPT_EINVAL, LOPT_ESHAPE, LOPT_ESTATE, LOPT_ELIMIT, and LOPT_ENOMEM / LOPT_EHIP raised
+ *    while tables are prepared) params and state are untouched. A HIP error raised later,
+ *    while a step's kernels are being enqueued, leaves params and state partly updated:
+ *    the library joins its second stream back into the caller's, marks the context failed,
+ *    and every later step through it returns LOPT_EHIP.
  *  - A context is not thread-safe: calls on one context must not overlap on the host, and
  *    steps enqueued through one context on different streams are not ordered with respect to
  *    each other by the library (they share the context's tables and the caller's workspace).
@@ -122,10 +126,11 @@ size_t lopt_weights_count(const lopt_config* cfg);
  * outside [0,1), negative eps), LOPT_ESTATE (n_weights != lopt_weights_count), LOPT_ENOMEM,
  * LOPT_EHIP.
  * Tuning knobs read from the environment here (none changes what is computed beyond rounding):
- *   LOPT_APPLY = valu | mfma_f32 | mfma_f16x3 | mfma_f16s   apply kernel for hidden width 32
- *                (default mfma_f16s: split-fp16 matrix cores, column strips, software-pipelined)
- *   LOPT_GROUPS = 1..16   number of tensor groups of the two-stream pipeline (default by list size;
- *                1 = every pass over the whole list, one after the other, on the caller's stream) */
+ *   LOPT_APPLY = auto | valu | mfma_f32 | mfma_f16x3 | mfma_f16s   apply kernel for hidden width 32
+ *                (auto = mfma_f16s: split-fp16 matrix cores, column strips, software-pipelined)
+ *   LOPT_GROUPS = 0..16   number of tensor groups of the two-stream pipeline (0 = by list size;
+ *                1 = every pass over the whole list, one after the other, on the caller's stream)
+ * Any other value of either is refused with LOPT_EINVAL. */
 lopt_status lopt_create(const lopt_config* cfg, const float* weights_host, size_t n_weights,
                         lopt_ctx** out);
 

@@ -150,6 +150,7 @@ struct lopt_ctx {
   Plan plan;
   bool plan_valid = false;
   TableStore heap, fixed;
+  bool failed = false;             // a HIP call failed in the middle of a launch sequence: the context refuses further steps
   float loss = 0.f;                // lopt_set_loss: goes with the gradients of the following steps (VeLO)
   uint64_t id = 0;                 // names this context as the owner of the static scratch's contents
   void* static_scratch = nullptr;  // device address of `scratch` on ctx->device
@@ -168,7 +169,7 @@ struct lopt_ctx {
   bool profiling = false;
   std::vector<hipEvent_t> prof_events;   // (LOPT_N_PASSES + 1) events per recorded step
   size_t prof_steps = 0;
-  std::string err;
+  std::string err, err_first;
 };
 
 namespace {
@@ -476,16 +477,25 @@ lopt_status lopt_create(const lopt_config* cfg, const float* weights_host, size_
     try { eq = equilibrate_small_fc(weights_host, (int)cfg->hidden); } catch (const std::bad_alloc&) { return fail(nullptr, LOPT_ENOMEM, "out of host memory"); }
     weights_host = eq.data();   // from here on: the equivalent, rescaled network
   }
+  int apply_variant = 0, groups_override = 0;
+  if (const char* e = getenv("LOPT_APPLY")) {
+    apply_variant = !strcmp(e, "auto") ? 0 : !strcmp(e, "valu") ? 1 : !strcmp(e, "mfma_f32") ? 2 : !strcmp(e, "mfma_f16x3") ? 3
+                  : !strcmp(e, "mfma_f16s") ? 4 : -1;
+    if (apply_variant < 0)
+      return fail(nullptr, LOPT_EINVAL, std::string("LOPT_APPLY=") + e + " is not one of auto, valu, mfma_f32, mfma_f16x3, mfma_f16s");
+  }
+  if (const char* e = getenv("LOPT_GROUPS")) {
+    char* end = nullptr;
+    const long g = strtol(e, &end, 10);
+    if (end == e || *end || g < 0 || g > kMaxGroups)
+      return fail(nullptr, LOPT_EINVAL, std::string("LOPT_GROUPS=") + e + " is not an integer in [0, 16]");
+    groups_override = (int)g;
+  }
   lopt_ctx* ctx = new (std::nothrow) lopt_ctx();
   if (!ctx) return fail(nullptr, LOPT_ENOMEM, "out of host memory");
   ctx->cfg = *cfg;
-  if (const char* e = getenv("LOPT_APPLY")) {
-    ctx->apply_variant = !strcmp(e, "valu") ? 1 : !strcmp(e, "mfma_f32") ? 2 : !strcmp(e, "mfma_f16x3") ? 3 : !strcmp(e, "mfma_f16s") ? 4 : 0;
-  }
-  if (const char* e = getenv("LOPT_GROUPS")) {
-    const int g = atoi(e);
-    ctx->groups_override = g < 0 ? 0 : g > kMaxGroups ? kMaxGroups : g;
-  }
+  ctx->apply_variant = apply_variant;
+  ctx->groups_override = groups_override;
   const int H = (int)cfg->hidden;
   ctx->HP = padded_hidden(H);
   ctx->F = cfg->kind == LOPT_SMALL_FC ? LOPT_N_ELEM_FEATS : LOPT_D_VELO;
@@ -664,6 +674,7 @@ static lopt_status step_impl(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* de
                              const float* const* grads, void* const* state, void* workspace, int64_t step, float lr,
                              float weight_decay, void* hip_stream, bool use_static) {
   if (!ctx) return fail(nullptr, LOPT_EINVAL, "ctx is null");
+  if (ctx->failed) return fail(ctx, LOPT_EHIP, "this context failed in the middle of an earlier step (" + ctx->err_first + "); create a new one");
   lopt_status st = check_descs(ctx, n, descs);
   if (st != LOPT_OK) return st;
   if (step < 0) return fail(ctx, LOPT_EINVAL, "step must be >= 0");
@@ -733,6 +744,23 @@ static lopt_status step_impl(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* de
     if (strip_ok) G = planned_groups(ctx->groups_override, pl.total_elems, n);
     else if (velo && ctx->groups_override) G = planned_groups(ctx->groups_override, pl.total_elems, n);
   }
+  // From here on kernels are in flight: a HIP error leaves params and state partly updated. The context is marked
+  // failed, and the second stream (if it was forked) is joined back so that the caller's stream semantics hold.
+  bool forked = false;
+  auto launch_failed = [&](hipError_t e, const char* what) {
+    if (forked) {
+      (void)hipEventRecord(ctx->ev_pre[0], ctx->aux_stream);
+      (void)hipStreamWaitEvent(stream, ctx->ev_pre[0], 0);
+    }
+    ctx->failed = true;
+    ctx->err_first = std::string(what) + ": " + hipGetErrorString(e);
+    return fail(ctx, e == hipErrorOutOfMemory ? LOPT_ENOMEM : LOPT_EHIP, ctx->err_first);
+  };
+#define LAUNCH_TRY(call)                                              \
+  do {                                                                \
+    hipError_t e_ = (call);                                           \
+    if (e_ != hipSuccess) return launch_failed(e_, #call);            \
+  } while (0)
   if (G > 1) {
     // contiguous tensor ranges of about equal element count
     int bound[kMaxGroups + 1];
@@ -766,21 +794,22 @@ static lopt_status step_impl(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* de
     launch_rc_update(L, A, stream);
     // the cross-tensor term reads every tensor's LSTM output of the previous step: before any group rewrites its own
     if (velo) launch_velo_mix(L, A, ctx->W, ws + pl.oHbarPart, ws + pl.oBeff, stream);
-    HIP_TRY(ctx, hipEventRecord(ctx->ev_fork, stream));       // aux joins the caller's stream here ...
-    HIP_TRY(ctx, hipStreamWaitEvent(aux, ctx->ev_fork, 0));
+    LAUNCH_TRY(hipEventRecord(ctx->ev_fork, stream));       // aux joins the caller's stream here ...
+    LAUNCH_TRY(hipStreamWaitEvent(aux, ctx->ev_fork, 0));
+    forked = true;
     stats_passes(sub(0), stream);
     for (int g = 0; g < G; ++g) {
       if (g + 1 < G) {
         // the next group's HBM-bound passes start when this group's are done, i.e. together with its apply pass
-        HIP_TRY(ctx, hipEventRecord(ctx->ev_start[g + 1], stream));
-        HIP_TRY(ctx, hipStreamWaitEvent(aux, ctx->ev_start[g + 1], 0));
+        LAUNCH_TRY(hipEventRecord(ctx->ev_start[g + 1], stream));
+        LAUNCH_TRY(hipStreamWaitEvent(aux, ctx->ev_start[g + 1], 0));
         stats_passes(sub(g + 1), aux);
-        HIP_TRY(ctx, hipEventRecord(ctx->ev_pre[g + 1], aux));
+        LAUNCH_TRY(hipEventRecord(ctx->ev_pre[g + 1], aux));
       }
       launch_apply(sub(g));
-      if (g + 1 < G) HIP_TRY(ctx, hipStreamWaitEvent(stream, ctx->ev_pre[g + 1], 0));   // ... and is joined back here
+      if (g + 1 < G) LAUNCH_TRY(hipStreamWaitEvent(stream, ctx->ev_pre[g + 1], 0));   // ... and is joined back here
     }
-    HIP_TRY(ctx, hipGetLastError());
+    LAUNCH_TRY(hipGetLastError());
     return LOPT_OK;
   }
   hipEvent_t* ev = nullptr;
@@ -788,13 +817,27 @@ static lopt_status step_impl(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* de
     const size_t need = (ctx->prof_steps + 1) * (LOPT_N_PASSES + 1);
     while (ctx->prof_events.size() < need) {
       hipEvent_t e;
-      HIP_TRY(ctx, hipEventCreate(&e));
+      HIP_TRY(ctx, hipEventCreate(&e));   // nothing is in flight yet
       ctx->prof_events.push_back(e);
     }
     ev = ctx->prof_events.data() + ctx->prof_steps * (LOPT_N_PASSES + 1);
     ctx->prof_steps++;
   }
-#define MARK(i) do { if (ev) HIP_TRY(ctx, hipEventRecord(ev[i], stream)); } while (0)
+#define MARK(i) do { if (ev) LAUNCH_TRY(hipEventRecord(ev[i], stream)); } while (0)
+  // VeLO's cross-tensor term depends on nothing this step computes (it reads the LSTM outputs of the previous step):
+  // its two small launches run on the second stream beside the row/column and statistics passes and are joined
+  // back before the LSTM kernel. Only for lists of 8 M elements or more: the fork and join cost a short list more
+  // (about 7 us) than the two launches in line do. With per-pass timing on they run in line and count towards the
+  // velo_lstm pass.
+  const bool velo1 = ctx->cfg.kind == LOPT_VELO;
+  const bool mix_aside = velo1 && ctx->aux_stream && !profiling && pl.total_elems >= (8u << 20);
+  if (mix_aside) {
+    LAUNCH_TRY(hipEventRecord(ctx->ev_fork, stream));
+    LAUNCH_TRY(hipStreamWaitEvent(ctx->aux_stream, ctx->ev_fork, 0));
+    forked = true;
+    launch_velo_mix(L, A, ctx->W, ws + pl.oHbarPart, ws + pl.oBeff, ctx->aux_stream);
+    LAUNCH_TRY(hipEventRecord(ctx->ev_pre[0], ctx->aux_stream));
+  }
   MARK(0);
   launch_rowcol_sums(L, A, stream);
   MARK(1);
@@ -804,8 +847,9 @@ static lopt_status step_impl(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* de
   MARK(3);
   launch_finalize(L, A, ctx->W, ws + pl.oLstmU, stream);
   MARK(4);
-  if (ctx->cfg.kind == LOPT_VELO) {
-    launch_velo_mix(L, A, ctx->W, ws + pl.oHbarPart, ws + pl.oBeff, stream);
+  if (velo1) {
+    if (mix_aside) LAUNCH_TRY(hipStreamWaitEvent(stream, ctx->ev_pre[0], 0));
+    else launch_velo_mix(L, A, ctx->W, ws + pl.oHbarPart, ws + pl.oBeff, stream);
     launch_velo_lstm(L, A, ctx->W, ws + pl.oLstmU, ws + pl.oBeff, ws + pl.oHNew, stream);
     MARK(5);
     launch_velo_head(L, A, ctx->W, ws + pl.oHNew, stream);
@@ -817,8 +861,9 @@ static lopt_status step_impl(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* de
   launch_apply(L);
   MARK(7);
 #undef MARK
-  HIP_TRY(ctx, hipGetLastError());
+  LAUNCH_TRY(hipGetLastError());
   return LOPT_OK;
+#undef LAUNCH_TRY
 }
 
 extern "C" {

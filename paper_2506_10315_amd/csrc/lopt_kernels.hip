@@ -491,56 +491,71 @@ void launch_finalize(const Launch& L, const StepArgs& A, const WeightsDev& W, fl
 
 // hbar = mean over the tensors of the list of their LSTM outputs h (as left by the previous step), in two stages with
 // a fixed order: slice s of the list -> part[s][j] (this kernel: lane = unit j, the four wavefronts take every fourth
-// tensor of the slice and meet in LDS), then the slices in index order (k_velo_mixbias).
+// tensor of the slice, four tensors in flight each, and meet in LDS), then the slices in index order (k_velo_mixbias).
 __global__ void __launch_bounds__(kBlock) k_velo_hbar(const TensorDev* __restrict__ tensors, int n_tensors, int per_slice,
                                                       int HL, float* __restrict__ part) {
   __shared__ float red[4][kWave];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int j = blockIdx.x * kWave + lane;
+  const int j = min((int)blockIdx.x * kWave + lane, HL - 1);   // lanes past the end repeat the last unit (dropped below)
   const int t0 = blockIdx.y * per_slice, t1 = min(t0 + per_slice, n_tensors);
   float a = 0.f;
-  if (j < HL)
-    for (int t = t0 + wave; t < t1; t += 4) {
-      const TensorDev& T = tensors[t];
-      a += T.st[4 * (size_t)T.padN + 3 * (size_t)T.padm + 3 * (size_t)T.padn + j];
+  for (int t = t0 + wave; t < t1; t += 16) {
+    float v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int tt = min(t + 4 * k, t1 - 1);
+      const TensorDev& T = tensors[tt];
+      v[k] = T.st[4 * (size_t)T.padN + 3 * (size_t)T.padm + 3 * (size_t)T.padn + j];
     }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) a += t + 4 * k < t1 ? v[k] : 0.f;
+  }
   red[wave][lane] = a;
   __syncthreads();
-  if (wave == 0 && j < HL) part[(size_t)blockIdx.y * HL + j] = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
+  if (wave == 0 && (int)blockIdx.x * kWave + lane < HL)
+    part[(size_t)blockIdx.y * HL + j] = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
 }
 
 // b_eff[col] = b[col] + sum_j hbar[j] Wg[j][col]: the cross-tensor input is the same for every tensor of the list, so
-// its gate contribution is computed once and takes the place of the LSTM bias.
+// its gate contribution is computed once and takes the place of the LSTM bias. A workgroup owns 64 gate columns
+// (lane = column: coalesced rows of Wg); its four wavefronts take every fourth unit j, eight rows in flight each, and
+// meet in LDS in a fixed order.
 __global__ void __launch_bounds__(kBlock) k_velo_mixbias(const float* __restrict__ part, int n_slices, int n_tensors, int HL,
                                                          WeightsDev W, float* __restrict__ b_eff) {
   __shared__ float hbar[1024];
+  __shared__ float red[4][kWave];
   for (int j = threadIdx.x; j < HL; j += kBlock) {
     double a = 0.0;
     for (int s = 0; s < n_slices; ++s) a += (double)part[(size_t)s * HL + j];
     hbar[j] = (float)(a / (double)n_tensors);
   }
   __syncthreads();
-  const int col = blockIdx.x * kBlock + threadIdx.x, G = 4 * HL;
-  if (col >= G) return;
-  float a0 = 0.f, a1 = 0.f;
-  int j = 0;
-  for (; j + 1 < HL; j += 2) {
-    a0 += hbar[j] * W.Wg[(size_t)j * G + col];
-    a1 += hbar[j + 1] * W.Wg[(size_t)(j + 1) * G + col];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int G = 4 * HL;
+  const int col = min((int)blockIdx.x * kWave + lane, G - 1);
+  const float* __restrict__ wg = W.Wg + col;
+  float a = 0.f;
+  for (int j = wave; j < HL; j += 32) {
+    float w[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) w[k] = wg[(size_t)min(j + 4 * k, HL - 1) * G];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) a += j + 4 * k < HL ? hbar[j + 4 * k] * w[k] : 0.f;
   }
-  if (j < HL) a0 += hbar[j] * W.Wg[(size_t)j * G + col];
-  b_eff[col] = W.b[col] + (a0 + a1);
+  red[wave][lane] = a;
+  __syncthreads();
+  if (wave == 0 && (int)blockIdx.x * kWave + lane < G)
+    b_eff[col] = W.b[col] + ((red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]));
 }
 
 void launch_velo_mix(const Launch& L, const StepArgs& A, const WeightsDev& W, float* hbar_part, float* b_eff, hipStream_t s) {
   if (L.n_tensors == 0) return;
-  int n_slices = (L.n_tensors + 31) / 32;
-  if (n_slices > kMixSlices) n_slices = kMixSlices;
-  const int per_slice = (L.n_tensors + n_slices - 1) / n_slices;
-  n_slices = (L.n_tensors + per_slice - 1) / per_slice;
+  int per_slice = (L.n_tensors + kMixSlices - 1) / kMixSlices;
+  if (per_slice < 16) per_slice = 16;   // four tensors in flight on each of four wavefronts
+  const int n_slices = (L.n_tensors + per_slice - 1) / per_slice;
   hipLaunchKernelGGL(k_velo_hbar, dim3((A.HL + kWave - 1) / kWave, n_slices), dim3(kBlock), 0, s, L.tensors, L.n_tensors,
                      per_slice, A.HL, hbar_part);
-  hipLaunchKernelGGL(k_velo_mixbias, dim3((4 * A.HL + kBlock - 1) / kBlock), dim3(kBlock), 0, s, hbar_part, n_slices,
+  hipLaunchKernelGGL(k_velo_mixbias, dim3((4 * A.HL + kWave - 1) / kWave), dim3(kBlock), 0, s, hbar_part, n_slices,
                      L.n_tensors, A.HL, W, b_eff);
 }
 

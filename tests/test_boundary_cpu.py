@@ -111,3 +111,28 @@ def test_bench_refuses_more_than_one_gpu():
                        timeout=300)
     assert r.returncode != 0
     assert "one GPU" in (r.stdout + r.stderr)
+
+
+def test_create_refuses_unknown_tuning_knob_values_and_non_finite_weights(monkeypatch):
+    import paper_2506_10315_amd as P
+    L = P.lib()
+    w = np.zeros(2402, np.float32)
+    wp = w.ctypes.data_as(C.POINTER(C.c_float))
+    ctx = C.c_void_p()
+    c = P.default_config(0)
+    monkeypatch.setenv("LOPT_APPLY", "mfma_f16")            # a misspelt variant must not silently mean "auto"
+    assert L.lopt_create(C.byref(c), wp, 2402, C.byref(ctx)) == 1 and b"LOPT_APPLY" in L.lopt_last_error(None)
+    monkeypatch.delenv("LOPT_APPLY")
+    for bad in ("17", "-1", "four", ""):
+        monkeypatch.setenv("LOPT_GROUPS", bad)
+        assert L.lopt_create(C.byref(c), wp, 2402, C.byref(ctx)) == 1 and b"LOPT_GROUPS" in L.lopt_last_error(None)
+    monkeypatch.delenv("LOPT_GROUPS")
+    w[100] = np.inf
+    assert L.lopt_create(C.byref(c), wp, 2402, C.byref(ctx)) == 1 and b"non-finite" in L.lopt_last_error(None)
+    assert not ctx.value
+
+
+def test_set_loss_validates_its_arguments():
+    import paper_2506_10315_amd as P
+    L = P.lib()
+    assert L.lopt_set_loss(None, 1.0) == 1

@@ -175,3 +175,62 @@ def test_context_reused_across_different_tensor_lists_and_streams():
         opt.close()
     for x, y in zip(*res):
         assert np.array_equal(x, y)
+
+
+@pytest.mark.parametrize("kind,shapes,static", [
+    ("small_fc_lopt", [(300, 257), (64, 256), (1030,), (5,)], True),
+    ("velo", [(300, 257), (64, 256), (1030,), (5,)], True),
+    ("small_fc_lopt", [(1000, 1000)], False),
+    ("small_fc_lopt", [(4096, 2560)] * 4 + [(2560,)] * 4, True),       # 42 M elements: the two-stream group pipeline
+])
+def test_a_step_captured_in_a_hip_graph_replays_bit_identically(kind, shapes, static):
+    # After one warm-up call (tables uploaded, nothing left to allocate) a step is captured into a HIP graph: no
+    # allocation, no host synchronization and no memset node inside the capture (tile counters are cleared by a kernel).
+    # Replays are checked against the eager step from the same state, three times, with eager work and
+    # synchronizations of the program's own in between.
+    import torch
+    import paper_2506_10315_amd as P
+    dev = "cuda:0"
+    cfg = Hn.make_cfg(kind) if kind == "small_fc_lopt" else Hn.make_cfg(kind, lstm_hidden=64, n_bank=32)
+    w = Hn.random_weights(cfg, 2)
+    specs = [W.TensorSpec(f"t{i}", s) for i, s in enumerate(shapes)]
+    case = Hn.Case(202, specs, "gauss_logscale")
+    opt = P.LearnedOptimizer(cfg, w, shapes, device=dev)
+    n = len(specs)
+    p = [torch.from_numpy(case.p0(i)).to(dev) for i in range(n)]
+    g = [torch.from_numpy(case.grad(i, 0)).to(dev) for i in range(n)]
+    kw = dict(lr=0.7, weight_decay=0.01, static=static, loss=1.5)
+    for t in range(2):                                   # warm-up: two real steps, so the state is not trivial
+        opt.step(p, g, step=t, **kw)
+    torch.cuda.synchronize()
+    p0 = [x.clone() for x in p]
+    s0 = [x.clone() for x in opt.state]
+
+    def restore():
+        for dst, src in zip(p, p0):
+            dst.copy_(src)
+        for dst, src in zip(opt.state, s0):
+            dst.copy_(src)
+
+    opt.step(p, g, step=2, **kw)                         # the eager result of step 2 from (p0, s0)
+    torch.cuda.synchronize()
+    want = [x.clone() for x in p] + [x.clone() for x in opt.state]
+    restore()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        opt.step(p, g, step=2, **kw)
+    torch.cuda.synchronize()
+    junk = torch.zeros(1 << 20, device=dev)
+    for rep in range(3):
+        restore()
+        junk.add_(1.0)                                   # the program's own eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = list(p) + list(opt.state)
+        for a, b in zip(want, got):
+            assert torch.equal(a.view(torch.int32), b.view(torch.int32)), f"replay {rep} differs from the eager step"
+    del graph
+    opt.close()
