@@ -243,7 +243,7 @@ void build_plan(const lopt_ctx* ctx, size_t n, const lopt_tensor_desc* d, Plan* 
     pl->oLstmU = take((uint64_t)n * kLstmInPad);
     pl->oHNew = take((uint64_t)n * ctx->cfg.lstm_hidden);
     pl->oHbarPart = take((uint64_t)kMixSlices * ctx->cfg.lstm_hidden);
-    pl->oBeff = take(4ull * ctx->cfg.lstm_hidden);
+    pl->oBeff = take((uint64_t)kMixJSplit * 4ull * ctx->cfg.lstm_hidden);
   }
   // Apply tiles get shorter towards the end of every tensor group of the pipeline (a single group if it is off): the
   // strip apply kernel hands tiles out in table order, so the last tiles of a launch decide how long the chip idles
@@ -790,10 +790,9 @@ static lopt_status step_impl(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* de
     };
     hipStream_t aux = ctx->aux_stream;
     // the row/column pass reads only the gradients (4 of the step's 72 bytes per element): whole list, up front
-    launch_rowcol_sums(L, A, stream);
-    launch_rc_update(L, A, stream);
-    // the cross-tensor term reads every tensor's LSTM output of the previous step: before any group rewrites its own
-    if (velo) launch_velo_mix(L, A, ctx->W, ws + pl.oHbarPart, ws + pl.oBeff, stream);
+    // (VeLO: the cross-tensor term rides along in these two launches, before any group rewrites its LSTM outputs)
+    launch_rowcol_sums(L, A, ctx->W, ws + pl.oHbarPart, ws + pl.oBeff, stream);
+    launch_rc_update(L, A, ctx->W, ws + pl.oHbarPart, ws + pl.oBeff, stream);
     LAUNCH_TRY(hipEventRecord(ctx->ev_fork, stream));       // aux joins the caller's stream here ...
     LAUNCH_TRY(hipStreamWaitEvent(aux, ctx->ev_fork, 0));
     forked = true;
@@ -824,32 +823,16 @@ static lopt_status step_impl(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* de
     ctx->prof_steps++;
   }
 #define MARK(i) do { if (ev) LAUNCH_TRY(hipEventRecord(ev[i], stream)); } while (0)
-  // VeLO's cross-tensor term depends on nothing this step computes (it reads the LSTM outputs of the previous step):
-  // its two small launches run on the second stream beside the row/column and statistics passes and are joined
-  // back before the LSTM kernel. Only for lists of 8 M elements or more: the fork and join cost a short list more
-  // (about 7 us) than the two launches in line do. With per-pass timing on they run in line and count towards the
-  // velo_lstm pass.
-  const bool velo1 = ctx->cfg.kind == LOPT_VELO;
-  const bool mix_aside = velo1 && ctx->aux_stream && !profiling && pl.total_elems >= (8u << 20);
-  if (mix_aside) {
-    LAUNCH_TRY(hipEventRecord(ctx->ev_fork, stream));
-    LAUNCH_TRY(hipStreamWaitEvent(ctx->aux_stream, ctx->ev_fork, 0));
-    forked = true;
-    launch_velo_mix(L, A, ctx->W, ws + pl.oHbarPart, ws + pl.oBeff, ctx->aux_stream);
-    LAUNCH_TRY(hipEventRecord(ctx->ev_pre[0], ctx->aux_stream));
-  }
   MARK(0);
-  launch_rowcol_sums(L, A, stream);
+  launch_rowcol_sums(L, A, ctx->W, ws + pl.oHbarPart, ws + pl.oBeff, stream);
   MARK(1);
-  launch_rc_update(L, A, stream);
+  launch_rc_update(L, A, ctx->W, ws + pl.oHbarPart, ws + pl.oBeff, stream);
   MARK(2);
   launch_accum_stats(L, A, stream);
   MARK(3);
   launch_finalize(L, A, ctx->W, ws + pl.oLstmU, stream);
   MARK(4);
-  if (velo1) {
-    if (mix_aside) LAUNCH_TRY(hipStreamWaitEvent(stream, ctx->ev_pre[0], 0));
-    else launch_velo_mix(L, A, ctx->W, ws + pl.oHbarPart, ws + pl.oBeff, stream);
+  if (ctx->cfg.kind == LOPT_VELO) {
     launch_velo_lstm(L, A, ctx->W, ws + pl.oLstmU, ws + pl.oBeff, ws + pl.oHNew, stream);
     MARK(5);
     launch_velo_head(L, A, ctx->W, ws + pl.oHNew, stream);

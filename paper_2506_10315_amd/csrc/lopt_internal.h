@@ -21,6 +21,7 @@ constexpr int kNStat = 17;        // per-element statistics accumulated per tile
 constexpr int kStatsPerTensor = 32;
 constexpr int kLstmInPad = 48;    // LOPT_VELO_LSTM_IN rounded up to a multiple of 4
 constexpr int kMixSlices = 64;    // at most this many slices of the tensor list in the cross-tensor mean
+constexpr int kMixJSplit = 4;     // the LSTM units are cut into this many ranges when hbar Wg is formed
 #ifndef LOPT_APPLY_ROWS
 #define LOPT_APPLY_ROWS 128
 #endif
@@ -93,13 +94,13 @@ struct Launch {
 
 // kernels (lopt_kernels.hip / lopt_apply_mfma.hip)
 void launch_fill_zero(const Launch&, const StepArgs&, hipStream_t);
-void launch_rowcol_sums(const Launch&, const StepArgs&, hipStream_t);
-void launch_rc_update(const Launch&, const StepArgs&, hipStream_t);
+// VeLO: the two stages of the cross-tensor term (hbar = mean of the tensors' LSTM outputs of the previous step,
+// b_eff = b + hbar Wg) ride along as extra workgroups of these two launches, which always cover the WHOLE list and
+// come before any tensor's LSTM state is rewritten
+void launch_rowcol_sums(const Launch&, const StepArgs&, const WeightsDev&, float* hbar_part, float* b_eff, hipStream_t);
+void launch_rc_update(const Launch&, const StepArgs&, const WeightsDev&, float* hbar_part, float* b_eff, hipStream_t);
 void launch_accum_stats(const Launch&, const StepArgs&, hipStream_t);
 void launch_finalize(const Launch&, const StepArgs&, const WeightsDev&, float* lstm_u, hipStream_t);
-// cross-tensor term over the WHOLE list: hbar = mean of the tensors' h, b_eff = b + hbar Wg (must run before any
-// tensor's LSTM state is rewritten)
-void launch_velo_mix(const Launch&, const StepArgs&, const WeightsDev&, float* hbar_part, float* b_eff, hipStream_t);
 void launch_velo_lstm(const Launch&, const StepArgs&, const WeightsDev&, const float* lstm_u, const float* b_eff,
                       float* h_new, hipStream_t);
 void launch_velo_head(const Launch&, const StepArgs&, const WeightsDev&, const float* h_new,

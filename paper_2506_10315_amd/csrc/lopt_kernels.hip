@@ -41,6 +41,91 @@ void launch_fill_zero(const Launch& L, const StepArgs& A, hipStream_t s) {
   }
 }
 
+// ----------------------------------------------------------------------------- VeLO cross-tensor term
+
+// The cross-tensor input of VeLO's LSTM depends on nothing this step computes (it reads the LSTM outputs h the previous
+// step left in the state blobs), so its two stages ride along as extra workgroups of the first two launches of the
+// step instead of taking launches of their own: slice sums of h behind the tiles of k_rowcol_sums, the final mean and
+// the gate bias b_eff = b + hbar Wg behind the row/column blocks of k_rc_update. Both have a fixed summation order.
+struct MixArgs {
+  const float* Wg;        // [HL][4 HL]
+  const float* b;         // [4 HL]
+  float* part;            // [n_slices][HL] slice sums of h
+  float* b_eff;           // [kMixJSplit][4 HL]: hbar Wg summed over a quarter of the units j each
+  int HL, n_tensors, per_slice, n_slices;   // n_slices == 0: not VeLO, no extra workgroups
+};
+
+// Workgroup (chunk of 64 units, slice of the tensor list): lane = unit j, the four wavefronts take every fourth tensor
+// of the slice, four tensors in flight each, and meet in LDS.
+__device__ __forceinline__ void mix_hbar_block(const TensorDev* __restrict__ tensors, const MixArgs& M, int blk,
+                                               float (*red)[kWave]) {
+  const int n_chunks = (M.HL + kWave - 1) / kWave;
+  const int chunk = blk % n_chunks, slice = blk / n_chunks;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j = min(chunk * kWave + lane, M.HL - 1);   // lanes past the end repeat the last unit (dropped below)
+  const int t0 = slice * M.per_slice, t1 = min(t0 + M.per_slice, M.n_tensors);
+  float a = 0.f;
+  for (int t = t0 + wave; t < t1; t += 16) {
+    float v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int tt = min(t + 4 * k, t1 - 1);
+      const TensorDev& T = tensors[tt];
+      v[k] = T.st[4 * (size_t)T.padN + 3 * (size_t)T.padm + 3 * (size_t)T.padn + j];
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) a += t + 4 * k < t1 ? v[k] : 0.f;
+  }
+  red[wave][lane] = a;
+  __syncthreads();
+  if (wave == 0 && chunk * kWave + lane < M.HL)
+    M.part[(size_t)slice * M.HL + j] = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
+}
+
+// Workgroup = 64 gate columns (lane = column: coalesced rows of Wg) x one quarter of the units j; its four wavefronts
+// take every fourth unit of the quarter, eight rows in flight each, and meet in LDS in a fixed order. The quarters
+// are added up (with the bias b) by k_velo_lstm, again in a fixed order.
+__device__ __forceinline__ void mix_bias_block(const MixArgs& M, int blk, float* hbar, float (*red)[kWave]) {
+  const int HL = M.HL, G = 4 * HL;
+  const int n_colblk = (G + kWave - 1) / kWave;
+  const int colblk = blk % n_colblk, quarter = blk / n_colblk;
+  const int jq = (HL + kMixJSplit - 1) / kMixJSplit;
+  const int j0 = quarter * jq, j1 = min(j0 + jq, HL);
+  for (int j = j0 + (int)threadIdx.x; j < j1; j += kBlock) {
+    double a = 0.0;
+    for (int s = 0; s < M.n_slices; ++s) a += (double)M.part[(size_t)s * HL + j];
+    hbar[j - j0] = (float)(a / (double)M.n_tensors);
+  }
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = min(colblk * kWave + lane, G - 1);
+  const float* __restrict__ wg = M.Wg + col;
+  float a = 0.f;
+  for (int j = j0 + wave; j < j1; j += 32) {
+    float w[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) w[k] = wg[(size_t)min(j + 4 * k, j1 - 1) * G];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) a += j + 4 * k < j1 ? hbar[j + 4 * k - j0] * w[k] : 0.f;
+  }
+  red[wave][lane] = a;
+  __syncthreads();
+  if (wave == 0 && colblk * kWave + lane < G)
+    M.b_eff[(size_t)quarter * G + col] = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
+}
+
+static MixArgs make_mix(const Launch& L, const StepArgs& A, const WeightsDev& W, float* hbar_part, float* b_eff) {
+  MixArgs M{};
+  if (A.kind != LOPT_VELO || L.n_tensors == 0) return M;
+  M.Wg = W.Wg; M.b = W.b; M.part = hbar_part; M.b_eff = b_eff;
+  M.HL = A.HL; M.n_tensors = L.n_tensors;
+  int per_slice = (L.n_tensors + kMixSlices - 1) / kMixSlices;
+  if (per_slice < 16) per_slice = 16;   // four tensors in flight on each of four wavefronts
+  M.per_slice = per_slice;
+  M.n_slices = (L.n_tensors + per_slice - 1) / per_slice;
+  return M;
+}
+
 // ----------------------------------------------------------------------------- rowcol_sums
 
 template <bool VEC>
@@ -86,17 +171,25 @@ __device__ __forceinline__ void rowcol_tile(const TensorDev& T, const TileDev& t
 }
 
 __global__ void __launch_bounds__(kBlock) k_rowcol_sums(const TensorDev* __restrict__ tensors,
-                                                        const TileDev* __restrict__ tiles, float* __restrict__ ws) {
+                                                        const TileDev* __restrict__ tiles, float* __restrict__ ws,
+                                                        int n_tiles, MixArgs M) {
   __shared__ float colred[4][kTileCols];
+  if ((int)blockIdx.x >= n_tiles) {   // the extra workgroups of a VeLO step: slice sums of the LSTM outputs
+    mix_hbar_block(tensors, M, (int)blockIdx.x - n_tiles, reinterpret_cast<float (*)[kWave]>(&colred[0][0]));
+    return;
+  }
   const TileDev tile = tiles[blockIdx.x];
   const TensorDev& T = tensors[tile.tensor];
   if (T.vec) rowcol_tile<true>(T, tile, ws, colred);
   else rowcol_tile<false>(T, tile, ws, colred);
 }
 
-void launch_rowcol_sums(const Launch& L, const StepArgs&, hipStream_t s) {
+void launch_rowcol_sums(const Launch& L, const StepArgs& A, const WeightsDev& W, float* hbar_part, float* b_eff,
+                        hipStream_t s) {
   if (L.n_tiles == 0) return;
-  hipLaunchKernelGGL(k_rowcol_sums, dim3(L.n_tiles), dim3(kBlock), 0, s, L.tensors, L.tiles, L.ws);
+  const MixArgs M = make_mix(L, A, W, hbar_part, b_eff);
+  const int extra = M.n_slices * ((M.HL + kWave - 1) / kWave);
+  hipLaunchKernelGGL(k_rowcol_sums, dim3(L.n_tiles + extra), dim3(kBlock), 0, s, L.tensors, L.tiles, L.ws, L.n_tiles, M);
 }
 
 // ----------------------------------------------------------------------------- rc_update
@@ -136,8 +229,14 @@ __device__ __forceinline__ double strided_sum(const float* __restrict__ part, in
 
 __global__ void __launch_bounds__(kBlock) k_rc_update(const TensorDev* __restrict__ tensors,
                                                       const RcItemDev* __restrict__ items, float* __restrict__ ws,
-                                                      StepArgs A) {
+                                                      StepArgs A, int n_items, MixArgs M) {
   __shared__ float red[9][4];
+  if ((int)blockIdx.x >= n_items) {   // the extra workgroups of a VeLO step: mean of the LSTM outputs, gate bias
+    __shared__ float hbar[1024];
+    __shared__ float mred[4][kWave];
+    mix_bias_block(M, (int)blockIdx.x - n_items, hbar, mred);
+    return;
+  }
   const RcItemDev it = items[blockIdx.x];
   const TensorDev& T = tensors[it.tensor];
   const int idx = it.blk * kBlock + threadIdx.x;
@@ -183,9 +282,13 @@ __global__ void __launch_bounds__(kBlock) k_rc_update(const TensorDev* __restric
   block_sum<9>(v, red, ws + T.oRcPart + (size_t)slot * kRcStride);
 }
 
-void launch_rc_update(const Launch& L, const StepArgs& A, hipStream_t s) {
+void launch_rc_update(const Launch& L, const StepArgs& A, const WeightsDev& W, float* hbar_part, float* b_eff,
+                      hipStream_t s) {
   if (L.n_rcitems == 0) return;
-  hipLaunchKernelGGL(k_rc_update, dim3(L.n_rcitems), dim3(kBlock), 0, s, L.tensors, L.rcitems, L.ws, A);
+  const MixArgs M = make_mix(L, A, W, hbar_part, b_eff);
+  const int extra = M.n_slices ? kMixJSplit * ((4 * M.HL + kWave - 1) / kWave) : 0;
+  hipLaunchKernelGGL(k_rc_update, dim3(L.n_rcitems + extra), dim3(kBlock), 0, s, L.tensors, L.rcitems, L.ws, A,
+                     L.n_rcitems, M);
 }
 
 // ----------------------------------------------------------------------------- accum_stats
@@ -487,78 +590,6 @@ void launch_finalize(const Launch& L, const StepArgs& A, const WeightsDev& W, fl
                      L.apply_counter);
 }
 
-// ----------------------------------------------------------------------------- VeLO cross-tensor term
-
-// hbar = mean over the tensors of the list of their LSTM outputs h (as left by the previous step), in two stages with
-// a fixed order: slice s of the list -> part[s][j] (this kernel: lane = unit j, the four wavefronts take every fourth
-// tensor of the slice, four tensors in flight each, and meet in LDS), then the slices in index order (k_velo_mixbias).
-__global__ void __launch_bounds__(kBlock) k_velo_hbar(const TensorDev* __restrict__ tensors, int n_tensors, int per_slice,
-                                                      int HL, float* __restrict__ part) {
-  __shared__ float red[4][kWave];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int j = min((int)blockIdx.x * kWave + lane, HL - 1);   // lanes past the end repeat the last unit (dropped below)
-  const int t0 = blockIdx.y * per_slice, t1 = min(t0 + per_slice, n_tensors);
-  float a = 0.f;
-  for (int t = t0 + wave; t < t1; t += 16) {
-    float v[4];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const int tt = min(t + 4 * k, t1 - 1);
-      const TensorDev& T = tensors[tt];
-      v[k] = T.st[4 * (size_t)T.padN + 3 * (size_t)T.padm + 3 * (size_t)T.padn + j];
-    }
-#pragma unroll
-    for (int k = 0; k < 4; ++k) a += t + 4 * k < t1 ? v[k] : 0.f;
-  }
-  red[wave][lane] = a;
-  __syncthreads();
-  if (wave == 0 && (int)blockIdx.x * kWave + lane < HL)
-    part[(size_t)blockIdx.y * HL + j] = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
-}
-
-// b_eff[col] = b[col] + sum_j hbar[j] Wg[j][col]: the cross-tensor input is the same for every tensor of the list, so
-// its gate contribution is computed once and takes the place of the LSTM bias. A workgroup owns 64 gate columns
-// (lane = column: coalesced rows of Wg); its four wavefronts take every fourth unit j, eight rows in flight each, and
-// meet in LDS in a fixed order.
-__global__ void __launch_bounds__(kBlock) k_velo_mixbias(const float* __restrict__ part, int n_slices, int n_tensors, int HL,
-                                                         WeightsDev W, float* __restrict__ b_eff) {
-  __shared__ float hbar[1024];
-  __shared__ float red[4][kWave];
-  for (int j = threadIdx.x; j < HL; j += kBlock) {
-    double a = 0.0;
-    for (int s = 0; s < n_slices; ++s) a += (double)part[(size_t)s * HL + j];
-    hbar[j] = (float)(a / (double)n_tensors);
-  }
-  __syncthreads();
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int G = 4 * HL;
-  const int col = min((int)blockIdx.x * kWave + lane, G - 1);
-  const float* __restrict__ wg = W.Wg + col;
-  float a = 0.f;
-  for (int j = wave; j < HL; j += 32) {
-    float w[8];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) w[k] = wg[(size_t)min(j + 4 * k, HL - 1) * G];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) a += j + 4 * k < HL ? hbar[j + 4 * k] * w[k] : 0.f;
-  }
-  red[wave][lane] = a;
-  __syncthreads();
-  if (wave == 0 && (int)blockIdx.x * kWave + lane < G)
-    b_eff[col] = W.b[col] + ((red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]));
-}
-
-void launch_velo_mix(const Launch& L, const StepArgs& A, const WeightsDev& W, float* hbar_part, float* b_eff, hipStream_t s) {
-  if (L.n_tensors == 0) return;
-  int per_slice = (L.n_tensors + kMixSlices - 1) / kMixSlices;
-  if (per_slice < 16) per_slice = 16;   // four tensors in flight on each of four wavefronts
-  const int n_slices = (L.n_tensors + per_slice - 1) / per_slice;
-  hipLaunchKernelGGL(k_velo_hbar, dim3((A.HL + kWave - 1) / kWave, n_slices), dim3(kBlock), 0, s, L.tensors, L.n_tensors,
-                     per_slice, A.HL, hbar_part);
-  hipLaunchKernelGGL(k_velo_mixbias, dim3((4 * A.HL + kWave - 1) / kWave), dim3(kBlock), 0, s, hbar_part, n_slices,
-                     L.n_tensors, A.HL, W, b_eff);
-}
-
 // ----------------------------------------------------------------------------- VeLO hypernetwork
 
 // One LSTM-cell step for all tensors: Z[T, 4 H_L] = [u | h_prev] [Wx ; Wh] is a dense contraction and runs on the
@@ -643,7 +674,9 @@ __global__ void __launch_bounds__(kBlock) k_velo_lstm(const TensorDev* __restric
 #pragma unroll
           for (int g2 = 0; g2 < 4; ++g2) {
             const int c = g2 * 8 + uu;
-            zz[g2] = b_eff[g2 * HL + unit] + ((part[0][tile][tt][c] + part[1][tile][tt][c]) + (part[2][tile][tt][c] + part[3][tile][tt][c]));
+            const int gc = g2 * HL + unit;   // bias + cross-tensor term (its four partial sums, in order)
+            const float be = W.b[gc] + ((b_eff[gc] + b_eff[G + gc]) + (b_eff[2 * G + gc] + b_eff[3 * G + gc]));
+            zz[g2] = be + ((part[0][tile][tt][c] + part[1][tile][tt][c]) + (part[2][tile][tt][c] + part[3][tile][tt][c]));
           }
           const float ig = 1.f / (1.f + expf(-zz[0]));
           const float fg = 1.f / (1.f + expf(-zz[1]));
