@@ -39,10 +39,10 @@ PASS_BYTES = {"rowcol_sums": 4, "accum_stats": 40, "apply": 28}
 # for a plain 256 MiB copy: 2.0 and 1.0), keyed by (element count of the list, kernel). A kernel or list that was
 # not profiled reports null. Source: profiles/hbm_traffic_vit_b16.md.
 MEASURED_TRAFFIC_BYTES = {
-    (86_567_656, "k_apply_f16s"): (1_044_752 * 2.0 + 338_455) * 1024,
+    (86_567_656, "k_apply_f16s"): (1_044_874 * 2.0 + 338_455) * 1024,
     (86_567_656, "k_apply_velo4"): (1_024_085 * 2.0 + 338_155) * 1024,
-    (86_567_656, "k_accum_stats"): (1_020_455 * 2.0 + 1_353_160) * 1024,
-    (86_567_656, "k_rowcol_sums"): (169_594 * 2.0 + 7_109) * 1024,
+    (86_567_656, "k_accum_stats"): (1_020_449 * 2.0 + 1_353_160) * 1024,
+    (86_567_656, "k_rowcol_sums"): (169_589 * 2.0 + 7_108) * 1024,
 }
 
 APPLY_KERNEL = {"auto": "k_apply_f16s", "mfma_f16s": "k_apply_f16s", "mfma_f16x3": "k_apply_f16x3",
