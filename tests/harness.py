@@ -11,7 +11,7 @@ TOL_PARAM = 1e-4      # max relative error on updated parameters (metric: oracle
 TOL_ACC = 1e-5        # on accumulators
 TOL_STATS = 2e-5      # on the feature statistics (fp32 sums over the tensor)
 TOL_DELTA = 1e-4      # on the update p_old - p_new itself, in the same metric, net of the fp32 rounding of p_new
-TOL_LSTM = 1e-4       # on VeLO's LSTM state (see compare_state)
+TOL_LSTM = 1e-5       # on VeLO's LSTM state: the accumulator bar (worst seen over the whole GPU suite: 7e-7)
 ORACLE_THREADS = 12   # independent tensors go through the oracle side by side (the oracle itself is untouched)
 
 
@@ -113,9 +113,9 @@ WORST_LSTM = [0.0]    # largest LSTM-state error seen by compare_state in this p
 
 
 def compare_state(gs, st, tag, tol=TOL_ACC):
-    """Accumulators to `tol`. VeLO's LSTM state (h, c) is not an accumulator of the feature tables: it is a function of
-    the logarithms of the fp32 statistics (each good to TOL_STATS) through ~1100-term fp32 gate sums, and it feeds back
-    into itself over the steps, so it is held to TOL_LSTM."""
+    """Accumulators to `tol`, VeLO's LSTM state (h, c) to TOL_LSTM (the same bar: it is a function of the logarithms of
+    the fp32 statistics through ~1100-term fp32 gate sums and feeds back into itself over the steps, and still stays
+    an order of magnitude inside it)."""
     worst = 0.0
     for key in ("M", "V", "r", "c") + (("h", "cl") if "h" in st else ()):
         e = O.rel_err(gs[key], st[key])
