@@ -4,11 +4,14 @@
 // fixed sequence of launches that each cover ALL tensors of the step through a table of
 // work items (one workgroup = one tile of one tensor):
 //   rowcol_sums  : per tile, sum of g^2 over the tile's columns (per row) and rows (per column)
+//                  (+ VeLO: extra workgroups sum the tensors' previous LSTM outputs, slice by slice)
 //   rc_update    : per row / per column: finish the means, update r_k, c_k, keep rsqrt(r_k+eps),
 //                  rsqrt(c_k+eps), and partial sums for the row/column-constant features
+//                  (+ VeLO: extra workgroups finish the cross-tensor mean and its gate contribution)
 //   accum_stats  : M_i, V update + per-tile sums of squares of the per-element features
 //   finalize     : per tensor, fixed-order reduction of all partials -> s_f, scale factors,
-//                  first MLP layer with the normalization folded in (small_fc_lopt), LSTM input (VeLO)
+//                  first MLP layer with the normalization folded in (small_fc_lopt), LSTM input incl. time and
+//                  loss features (VeLO)
 //   velo_lstm, velo_head : the per-tensor hypernetwork (VeLO only)
 //   apply        : rebuild features, MLP, exponentiated update (lopt_apply_mfma.hip has the
 //                  matrix-core variant for hidden width 32)
@@ -227,10 +230,39 @@ __device__ __forceinline__ double strided_sum(const float* __restrict__ part, in
   return acc;
 }
 
+// The same sum formed by the whole workgroup (for one row or column at a time): thread t adds the terms t, t + 256, ...
+// in index order, then a fixed tree over the 256 threads. Every thread gets the result. For tensors of extreme aspect
+// ratio (a 1 x 2^28 vector has a million column tiles): one lane summing them all would take milliseconds.
+__device__ __forceinline__ double strided_sum_coop(const float* __restrict__ part, int count, size_t stride, double* tree) {
+  double a = 0.0;
+  int j = threadIdx.x;
+  for (; j + 7 * kBlock < count; j += 8 * kBlock) {
+    float t[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) t[k] = part[(size_t)(j + k * kBlock) * stride];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) a += (double)t[k];
+  }
+  for (; j < count; j += kBlock) a += (double)part[(size_t)j * stride];
+  __syncthreads();   // the previous use of the tree is over
+  tree[threadIdx.x] = a;
+  __syncthreads();
+  for (int w = kBlock / 2; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) tree[threadIdx.x] += tree[threadIdx.x + w];
+    __syncthreads();
+  }
+  return tree[0];
+}
+
+// A block of rows (or columns) takes the cooperative sum when there are at least 64 partials per row of the block and
+// more than 512 in all (decided by the shapes alone, so a given tensor list always takes the same path).
+__device__ __forceinline__ bool rc_sum_coop(int count, int valid) { return count > 512 && count >= 64 * valid; }
+
 __global__ void __launch_bounds__(kBlock) k_rc_update(const TensorDev* __restrict__ tensors,
                                                       const RcItemDev* __restrict__ items, float* __restrict__ ws,
                                                       StepArgs A, int n_items, MixArgs M) {
   __shared__ float red[9][4];
+  __shared__ double tree[kBlock];
   if ((int)blockIdx.x >= n_items) {   // the extra workgroups of a VeLO step: mean of the LSTM outputs, gate bias
     __shared__ float hbar[1024];
     __shared__ float mred[4][kWave];
@@ -244,9 +276,20 @@ __global__ void __launch_bounds__(kBlock) k_rc_update(const TensorDev* __restric
 #pragma unroll
   for (int q = 0; q < 9; ++q) v[q] = 0.f;
   float* st = T.st;
+  const int dim = it.is_col ? T.n : T.m, count = it.is_col ? T.nrt : T.nct;
+  const int valid = min(kBlock, dim - it.blk * kBlock);
+  const float* __restrict__ pbase = ws + (it.is_col ? T.oColPart : T.oRowPart) + (size_t)it.blk * kBlock;
+  double acc = 0.0;
+  if (rc_sum_coop(count, valid)) {   // workgroup-uniform
+    for (int i = 0; i < valid; ++i) {
+      const double v1 = strided_sum_coop(pbase + i, count, (size_t)dim, tree);
+      if ((int)threadIdx.x == i) acc = v1;
+    }
+  } else if (idx < dim) {
+    acc = strided_sum(pbase + threadIdx.x, count, (size_t)dim);
+  }
   if (!it.is_col) {
     if (idx < T.m) {
-      const double acc = strided_sum(ws + T.oRowPart + idx, T.nct, (size_t)T.m);
       const float R = (float)(acc / (double)T.n);
 #pragma unroll
       for (int k = 0; k < 3; ++k) {
@@ -263,7 +306,6 @@ __global__ void __launch_bounds__(kBlock) k_rc_update(const TensorDev* __restric
     }
   } else {
     if (idx < T.n) {
-      const double acc = strided_sum(ws + T.oColPart + idx, T.nrt, (size_t)T.n);
       const float C = (float)(acc / (double)T.m);
 #pragma unroll
       for (int k = 0; k < 3; ++k) {
@@ -704,35 +746,44 @@ void launch_velo_lstm(const Launch& L, const StepArgs& A, const WeightsDev& W, c
 
 // Partial matrix-vector product for the hypernetwork head: out[w][c0 + 64 c + lane] = sum over rows
 // k = w, w+nw, ... of x[k] * M[k][col], for the four columns c = 0..3 of this lane. Columns past the
-// end are clamped for the loads (their results are never read); two rows per trip keep eight
-// independent coalesced loads in flight.
+// end are clamped for the loads (their results are never read); four rows per trip keep sixteen
+// independent coalesced loads in flight (the kernel is bound by their latency).
 __device__ __forceinline__ void matvec4(const float* __restrict__ x, int n_in, const float* __restrict__ M, int ld,
                                         int c0, int wave, int nw, int lane, float* __restrict__ part, int W64) {
   const float* wp[4];
-  float acc0[4], acc1[4];
+  float acc[4][4];
 #pragma unroll
   for (int c = 0; c < 4; ++c) {
     const int col = c0 + 64 * c + lane;
     wp[c] = M + (col < ld ? col : ld - 1);
-    acc0[c] = acc1[c] = 0.f;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) acc[r][c] = 0.f;
   }
   int k = wave;
-  for (; k + nw < n_in; k += 2 * nw) {
-    const float x0 = x[k], x1 = x[k + nw];
-    float w0[4], w1[4];
+  for (; k + 3 * nw < n_in; k += 4 * nw) {
+    float xv[4], w[4][4];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) { w0[c] = wp[c][(size_t)k * ld]; w1[c] = wp[c][(size_t)(k + nw) * ld]; }
+    for (int r = 0; r < 4; ++r) {
+      xv[r] = x[k + r * nw];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) { acc0[c] += x0 * w0[c]; acc1[c] += x1 * w1[c]; }
+      for (int c = 0; c < 4; ++c) w[r][c] = wp[c][(size_t)(k + r * nw) * ld];
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) acc[r][c] += xv[r] * w[r][c];
   }
-  if (k < n_in) {
+  for (int r = 0; k < n_in; k += nw, ++r) {   // at most three rows left
     const float x0 = x[k];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) acc0[c] += x0 * wp[c][(size_t)k * ld];
+    for (int c = 0; c < 4; ++c) {
+      const float wv = wp[c][(size_t)k * ld];
+      if (r == 0) acc[0][c] += x0 * wv; else if (r == 1) acc[1][c] += x0 * wv; else acc[2][c] += x0 * wv;
+    }
   }
 #pragma unroll
   for (int c = 0; c < 4; ++c)
-    if (c0 + 64 * c < W64) part[wave * W64 + c0 + 64 * c + lane] = acc0[c] + acc1[c];
+    if (c0 + 64 * c < W64) part[wave * W64 + c0 + 64 * c + lane] = (acc[0][c] + acc[1][c]) + (acc[2][c] + acc[3][c]);
 }
 
 // Head of the hypernetwork for one tensor: alpha = h W_a + b_a, theta = alpha B, written as the

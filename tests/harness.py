@@ -182,7 +182,11 @@ def run_free(case: Case, cfg, weights, steps, lr_fn=lambda t: 1.0, wd=0.0, check
                 if check_stats:
                     k = ocfg.n_normalized
                     s_g = stats[i].cpu().numpy()[:k].astype(np.float64)
-                    s_o = infos[i]["stats"][:k]
+                    s_o = infos[i]["stats"][:k].copy()
+                    # feature 1 is the parameter itself: free-running, the two sides' parameters differ within
+                    # TOL_PARAM, which alone moves mean(p^2) by up to twice that. The reduction is checked against the
+                    # mean square of the GPU's own parameters before the step (the drift is the parameter check's job)
+                    s_o[1] = O.compute_squared_average(old_gpu[i].astype(np.float64).reshape(-1, 1))[0]
                     # a statistic acts only through s + eps_norm (fp32 cannot hold s below ~1e-45 anyway)
                     en = ocfg.eps_norm
                     rel = np.abs(s_g - s_o) / (np.abs(s_o) + en)
