@@ -131,6 +131,8 @@ struct Plan {
   std::vector<size_t> state_bytes;
   uint64_t oLstmU = 0, oHNew = 0;   // VeLO scratch (floats)
   uint64_t oHbarPart = 0, oBeff = 0; // VeLO cross-tensor term: slice sums of h, gate bias with the term added
+  uint64_t oAlpha = 0, oTheta = 0;   // VeLO, long lists: bank coefficients [T][K] and per-tensor MLPs [T][P]
+  bool head_batched = false;
   uint64_t oCounters = 0;           // kMaxGroups ints: tile counters of the strip-form apply kernel
   uint64_t ws_floats = 0;
 };
@@ -244,6 +246,11 @@ void build_plan(const lopt_ctx* ctx, size_t n, const lopt_tensor_desc* d, Plan* 
     pl->oHNew = take((uint64_t)n * ctx->cfg.lstm_hidden);
     pl->oHbarPart = take((uint64_t)kMixSlices * ctx->cfg.lstm_hidden);
     pl->oBeff = take((uint64_t)kMixJSplit * 4ull * ctx->cfg.lstm_hidden);
+    pl->head_batched = n >= (size_t)kHeadBatchMin;
+    if (pl->head_batched) {
+      pl->oAlpha = take((uint64_t)n * ctx->cfg.n_bank);
+      pl->oTheta = take((uint64_t)n * (uint64_t)ctx->P);
+    }
   }
   // Apply tiles get shorter towards the end of every tensor group of the pipeline (a single group if it is off): the
   // strip apply kernel hands tiles out in table order, so the last tiles of a launch decide how long the chip idles
@@ -785,7 +792,8 @@ static lopt_status step_impl(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* de
       launch_finalize(S, A, ctx->W, ws + pl.oLstmU, s);
       if (velo) {
         launch_velo_lstm(S, A, ctx->W, ws + pl.oLstmU, ws + pl.oBeff, ws + pl.oHNew, s);
-        launch_velo_head(S, A, ctx->W, ws + pl.oHNew, s);
+        launch_velo_head(S, A, ctx->W, ws + pl.oHNew, pl.head_batched ? ws + pl.oAlpha : nullptr,
+                         pl.head_batched ? ws + pl.oTheta : nullptr, s);
       }
     };
     hipStream_t aux = ctx->aux_stream;
@@ -835,7 +843,8 @@ static lopt_status step_impl(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* de
   if (ctx->cfg.kind == LOPT_VELO) {
     launch_velo_lstm(L, A, ctx->W, ws + pl.oLstmU, ws + pl.oBeff, ws + pl.oHNew, stream);
     MARK(5);
-    launch_velo_head(L, A, ctx->W, ws + pl.oHNew, stream);
+    launch_velo_head(L, A, ctx->W, ws + pl.oHNew, pl.head_batched ? ws + pl.oAlpha : nullptr,
+                     pl.head_batched ? ws + pl.oTheta : nullptr, stream);
     MARK(6);
   } else {
     MARK(5);

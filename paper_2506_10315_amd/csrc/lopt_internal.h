@@ -21,6 +21,7 @@ constexpr int kNStat = 17;        // per-element statistics accumulated per tile
 constexpr int kStatsPerTensor = 32;
 constexpr int kLstmInPad = 48;    // LOPT_VELO_LSTM_IN rounded up to a multiple of 4
 constexpr int kMixSlices = 64;    // at most this many slices of the tensor list in the cross-tensor mean
+constexpr int kHeadBatchMin = 1024;  // tensor lists from this length on take the batched form of the hypernetwork head
 constexpr int kMixJSplit = 4;     // the LSTM units are cut into this many ranges when hbar Wg is formed
 #ifndef LOPT_APPLY_ROWS
 #define LOPT_APPLY_ROWS 128
@@ -103,8 +104,8 @@ void launch_accum_stats(const Launch&, const StepArgs&, hipStream_t);
 void launch_finalize(const Launch&, const StepArgs&, const WeightsDev&, float* lstm_u, hipStream_t);
 void launch_velo_lstm(const Launch&, const StepArgs&, const WeightsDev&, const float* lstm_u, const float* b_eff,
                       float* h_new, hipStream_t);
-void launch_velo_head(const Launch&, const StepArgs&, const WeightsDev&, const float* h_new,
-                      hipStream_t);
+void launch_velo_head(const Launch&, const StepArgs&, const WeightsDev&, const float* h_new, float* alpha,
+                      float* theta, hipStream_t);
 void launch_apply_small_fc(const Launch&, const StepArgs&, const WeightsDev&, hipStream_t);
 void launch_apply_velo(const Launch&, const StepArgs&, const WeightsDev&, hipStream_t);
 bool apply_mfma_available(const StepArgs&);

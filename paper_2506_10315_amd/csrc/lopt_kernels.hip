@@ -849,8 +849,121 @@ __global__ void __launch_bounds__(1024) k_velo_head(const TensorDev* __restrict_
   }
 }
 
-void launch_velo_head(const Launch& L, const StepArgs& A, const WeightsDev& W, const float* h_new, hipStream_t s) {
+// ---- the head for long tensor lists: alpha = H' W_a + b_a and theta = alpha B as two batched products on the matrix
+// cores (fp32), then one small workgroup per tensor that scatters theta into the prepared layout.
+
+// Y[r][c] = bias[c] + sum_k X[r][k] Wm[k][c] with exact fp32 products (v_mfma_f32_32x32x2_f32), the scheme of
+// k_velo_lstm: a workgroup owns 32 rows x 64 columns (two 32-column tiles), its four wavefronts split the k range and
+// meet in LDS in a fixed order. Lane (k-half, i) holds X[row i][2p + k-half] (A operand) and Wm[2p + k-half][column i] (B
+// operand); loads are unconditional (rows, columns and k clamped, surplus k multiplied by 0).
+__global__ void __launch_bounds__(kBlock) k_rows_matmul(const float* __restrict__ X, int ldx, int n_rows, int n_in,
+                                                        const float* __restrict__ Wm, int ldw, int n_cols,
+                                                        const float* __restrict__ bias, float* __restrict__ Y, int ldy) {
+  __shared__ float part[4][2][32][32];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int khalf = lane >> 5, l32 = lane & 31;
+  const int r0 = blockIdx.x * 32, c0 = blockIdx.y * 64;
+  const float* __restrict__ xrow = X + (size_t)min(r0 + l32, n_rows - 1) * ldx;
+  const int ca = min(c0 + l32, n_cols - 1), cb = min(c0 + 32 + l32, n_cols - 1);
+  f32x16_l acc0, acc1;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) { acc0[v] = 0.f; acc1[v] = 0.f; }
+  const int n_pairs = (n_in + 1) / 2;
+  const int per_wave = (n_pairs + 3) / 4;
+  const int p_begin = wave * per_wave, p_end = min(p_begin + per_wave, n_pairs);
+  for (int pb = p_begin; pb < p_end; pb += kLstmPairsPerTrip) {
+    float a[kLstmPairsPerTrip], b0[kLstmPairsPerTrip], b1[kLstmPairsPerTrip];
+#pragma unroll
+    for (int j = 0; j < kLstmPairsPerTrip; ++j) {
+      const int pp = pb + j < p_end ? pb + j : p_end - 1;   // a repeated pair is multiplied by 0 below
+      const int k = 2 * pp + khalf;
+      const int kc = k < n_in ? k : n_in - 1;
+      const float keep = (pb + j < p_end && k < n_in) ? 1.f : 0.f;
+      a[j] = xrow[kc] * keep;
+      b0[j] = Wm[(size_t)kc * ldw + ca];
+      b1[j] = Wm[(size_t)kc * ldw + cb];
+    }
+#pragma unroll
+    for (int j = 0; j < kLstmPairsPerTrip; ++j) {
+      acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a[j], b0[j], acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a[j], b1[j], acc1, 0, 0, 0);
+    }
+  }
+  // accumulator register v of lane (k-half, c) is row 8 (v / 4) + 4 k-half + v % 4, column c
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int row = 8 * (v >> 2) + 4 * khalf + (v & 3);
+    part[wave][0][row][l32] = acc0[v];
+    part[wave][1][row][l32] = acc1[v];
+  }
+  __syncthreads();
+  const int rr = threadIdx.x >> 3, cc = threadIdx.x & 7;
+  if (r0 + rr < n_rows) {
+#pragma unroll
+    for (int tile = 0; tile < 2; ++tile)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int cl = 8 * q + cc, col = c0 + 32 * tile + cl;
+        if (col < n_cols)
+          Y[(size_t)(r0 + rr) * ldy + col] = (bias ? bias[col] : 0.f) + ((part[0][tile][rr][cl] + part[1][tile][rr][cl]) +
+                                                                          (part[2][tile][rr][cl] + part[3][tile][rr][cl]));
+      }
+  }
+}
+
+// One workgroup per tensor: new h into the state, step-size multiplier, theta[P] scattered into the prepared layout.
+__global__ void __launch_bounds__(kBlock) k_velo_head_scatter(const TensorDev* __restrict__ tensors, float* __restrict__ ws,
+                                                              StepArgs A, WeightsDev W, const float* __restrict__ h_new,
+                                                              const float* __restrict__ theta) {
+  __shared__ float s_lam;
+  const TensorDev& T = tensors[blockIdx.x];
+  const int HL = A.HL, H = A.H, HP = A.HP, F = LOPT_D_VELO, P = A.P;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float* hstate = T.st + 4 * (size_t)T.padN + 3 * (size_t)T.padm + 3 * (size_t)T.padn;
+  const float* __restrict__ hn = h_new + (size_t)blockIdx.x * HL;
+  for (int i = threadIdx.x; i < HL; i += kBlock) hstate[i] = hn[i];
+  float* prep = ws + T.oPrep;
+  const int prep_n = (F + 1) * HP + HP * HP + HP + 2 * HP + 2;
+  for (int i = threadIdx.x; i < prep_n; i += kBlock) prep[i] = 0.f;   // the padding must be zero
+  if (wave == 0) {
+    float a = 0.f;
+    for (int i = lane; i < HL; i += kWave) a += hn[i] * W.ws[i];
+    a = wave_sum(a);
+    if (lane == 0) s_lam = expf(a + W.bs[0]);
+  }
+  __syncthreads();
+  const float* scale = ws + T.oScale;
+  const float* __restrict__ th_row = theta + (size_t)blockIdx.x * P;
+  for (int i = threadIdx.x; i < P; i += kBlock) {
+    float th = th_row[i];
+    int o = i, dst;
+    if (o < F * H) { const int f = o / H, u = o - f * H; dst = f * HP + u; th *= scale[f]; }
+    else if ((o -= F * H) < H) dst = F * HP + o;
+    else if ((o -= H) < H * H) { const int a = o / H, u = o - a * H; dst = (F + 1) * HP + a * HP + u; }
+    else if ((o -= H * H) < H) dst = (F + 1) * HP + HP * HP + o;
+    else if ((o -= H) < 2 * H) { dst = (F + 1) * HP + HP * HP + HP + o; if (!(o & 1)) th *= s_lam; }   // W3[a][0]: direction
+    else { o -= 2 * H; dst = (F + 1) * HP + HP * HP + HP + 2 * HP + o; if (o == 0) th *= s_lam; }       // b3[0]
+    prep[dst] = th;
+  }
+}
+
+// alpha / theta: scratch of n_tensors x K and n_tensors x P floats for the batched form, null for lists below
+// kHeadBatchMin tensors (one workgroup per tensor then does everything; cheaper in launches, dearer in weight reads).
+void launch_velo_head(const Launch& L, const StepArgs& A, const WeightsDev& W, const float* h_new, float* alpha,
+                      float* theta, hipStream_t s) {
   if (L.n_tensors == 0) return;
+  if (alpha && theta && L.n_tensors >= kHeadBatchMin) {
+    const int T = L.n_tensors;
+    const float* hn = h_new + (size_t)L.tensor0 * A.HL;
+    float* al = alpha + (size_t)L.tensor0 * A.K;
+    float* th = theta + (size_t)L.tensor0 * A.P;
+    hipLaunchKernelGGL(k_rows_matmul, dim3((T + 31) / 32, (A.K + 63) / 64), dim3(kBlock), 0, s, hn, A.HL, T, A.HL, W.Wa, A.K,
+                       A.K, W.ba, al, A.K);
+    hipLaunchKernelGGL(k_rows_matmul, dim3((T + 31) / 32, (A.P + 63) / 64), dim3(kBlock), 0, s, al, A.K, T, A.K, W.B, A.P,
+                       A.P, (const float*)nullptr, th, A.P);
+    hipLaunchKernelGGL(k_velo_head_scatter, dim3(T), dim3(kBlock), 0, s, L.tensors + L.tensor0, L.ws, A, W, hn, th);
+    return;
+  }
   const int W64 = ((A.K > A.P ? A.K : A.P) + 63) & ~63;
   int nw = 16;  // wavefronts per workgroup = ways the reductions are split; bounded by 48 KB of partials
   while (nw > 1 && (size_t)nw * W64 * sizeof(float) > 48 * 1024) nw >>= 1;

@@ -41,6 +41,19 @@ def test_velo_odd_shapes(hidden, lstm_hidden, n_bank):
     Hn.run_free(Hn.Case(102, _specs(ODD_SHAPES), "gauss_logscale"), cfg, w, 4, lr_fn=lambda t: 0.5, wd=0.01)
 
 
+@pytest.mark.parametrize("hidden,lstm_hidden,n_bank", [(3, 33, 5), (4, 512, 256)])
+def test_velo_long_list_takes_the_batched_hypernetwork_head(hidden, lstm_hidden, n_bank):
+    # from 1024 tensors on the head of the hypernetwork runs as two batched matrix products and a scatter kernel
+    # instead of one workgroup per tensor: 1100 tensors (ragged last block of 32), odd and default widths
+    cfg = Hn.make_cfg("velo", hidden=hidden, lstm_hidden=lstm_hidden, n_bank=n_bank)
+    w = Hn.random_weights(cfg, seed=9)
+    r = np.random.default_rng(77)
+    shapes = [(int(r.integers(1, 40)),) for _ in range(1090)] + [(7, 13), (64, 256), (3, 1), (130, 260)] * 2 + [(33,), (5,)]
+    assert len(shapes) == 1100
+    worst = Hn.run_free(Hn.Case(109, _specs(shapes), "gauss_logscale"), cfg, w, 3, lr_fn=lambda t: 0.5, wd=0.01)
+    assert worst["param"] <= Hn.TOL_PARAM
+
+
 def test_velo_config1_shapes_free_running_with_clip_active():
     # gradients of order 0.1 so that the clipped-gradient feature differs from the gradient
     cfg = Hn.make_cfg("velo")
