@@ -45,10 +45,8 @@ MEASURED_TRAFFIC_BYTES = {
     (86_567_656, "k_rowcol_sums"): (169_589 * 2.0 + 7_108) * 1024,
 }
 
-APPLY_KERNEL = {"auto": "k_apply_f16s", "mfma_f16s": "k_apply_f16s", "mfma_f16x3": "k_apply_f16x3",
-                "mfma_f32": "k_apply_mfma", "valu": "k_apply"}
+APPLY_KERNEL = {"auto": "k_apply_f16s", "mfma_f16s": "k_apply_f16s", "mfma_f32": "k_apply_mfma", "valu": "k_apply"}
 APPLY_ARITH = {"k_apply_f16s": "fp16 hi+lo operands, 3 MFMA terms per product, fp32 accumulate (column strips, software-pipelined)",
-               "k_apply_f16x3": "fp16 hi+lo operands, 3 MFMA terms per product, fp32 accumulate (row form)",
                "k_apply_mfma": "fp32 MFMA", "k_apply": "fp32 vector ALU",
                "k_apply_velo4": "fp32 4x4x1 MFMA, per-tensor weights"}
 
@@ -183,7 +181,7 @@ def measure(wl, config_id, steps, warmup, device_draws=False, graph=False):
     hbm_gbs = PASS_BYTES.get(dominant, 0) * n_el / dur_s / 1e9
     roofline = {"kernel": kernel, "avg_launch_ms": pass_ms[dominant]}
     if dominant == "apply" and optimizer == "small_fc_lopt" and kernel != "k_apply":
-        peak_tf = MFMA_F16_PEAK_TFLOPS if kernel in ("k_apply_f16s", "k_apply_f16x3") else MFMA_F32_PEAK_TFLOPS
+        peak_tf = MFMA_F16_PEAK_TFLOPS if kernel == "k_apply_f16s" else MFMA_F32_PEAK_TFLOPS
         tflops = APPLY_FLOP_SMALL_FC * n_el / dur_s / 1e12
         t_hbm = PASS_BYTES["apply"] * n_el / (HBM_PEAK_GBS * 1e9)
         t_mfma = APPLY_FLOP_SMALL_FC * n_el / (peak_tf * 1e12)
@@ -224,7 +222,7 @@ def measure(wl, config_id, steps, warmup, device_draws=False, graph=False):
 
 
 def dtype_of(optimizer, apply_kernel):
-    if optimizer == "small_fc_lopt" and apply_kernel in ("k_apply_f16s", "k_apply_f16x3"):
+    if optimizer == "small_fc_lopt" and apply_kernel == "k_apply_f16s":
         return "f32 storage and arithmetic; MLP contraction as 3 fp16 MFMA terms on hi+lo operand pairs, fp32 accumulate"
     return "f32"
 

@@ -67,6 +67,15 @@ typedef enum {
 
 typedef enum { LOPT_SMALL_FC = 0, LOPT_VELO = 1 } lopt_kind;
 
+/* Apply kernel for small_fc_lopt with hidden width 32 (other widths and VeLO have one kernel each; VeLO honours
+ * LOPT_APPLY_VALU). None changes what is computed beyond rounding. */
+typedef enum {
+  LOPT_APPLY_AUTO = 0,      /* = LOPT_APPLY_MFMA_F16S */
+  LOPT_APPLY_VALU = 1,      /* fp32 vector ALU */
+  LOPT_APPLY_MFMA_F32 = 2,  /* fp32 matrix cores */
+  LOPT_APPLY_MFMA_F16S = 3  /* matrix cores on fp16 hi+lo operand pairs, fp32 accumulate; column strips, software-pipelined */
+} lopt_apply_kernel;
+
 /* Number of time features tanh(t/x), x in {1,3,10,30,100,300,1e3,3e3,1e4,3e4,1e5}
  * (feature table of small_fc_lopt, row "Time Features"). */
 #define LOPT_N_TIME 11
@@ -97,6 +106,9 @@ typedef struct {
   float step_mult;      /* beta in the same formula; paper: 0.01 */
   uint32_t lstm_hidden; /* VeLO only: LSTM width H_L (1..1024) */
   uint32_t n_bank;      /* VeLO only: number K of weight-bank rows (1..1024) */
+  uint32_t apply_kernel; /* lopt_apply_kernel; 0 = automatic */
+  uint32_t groups;      /* tensor groups of the two-stream pipeline, 1..16 (1 = every pass over the whole list, one after
+                           the other, on the caller's stream); 0 = by list size */
 } lopt_config;
 
 typedef struct {
@@ -107,7 +119,7 @@ typedef struct {
 
 /* Fill *cfg with the defaults for `kind`: decays {0.9,0.99,0.999}, 0.999, {0.9,0.99,0.999};
  * eps_acc 1e-16; eps_norm 1e-30; alpha = beta = 0.01; hidden 32 (small_fc_lopt) or 4 (VeLO);
- * lstm_hidden 512, n_bank 256. Returns LOPT_EINVAL for a null cfg or unknown kind. */
+ * lstm_hidden 512, n_bank 256; apply_kernel and groups automatic. Returns LOPT_EINVAL for a null cfg or unknown kind. */
 lopt_status lopt_default_config(uint32_t kind, lopt_config* cfg);
 
 /* Number of floats lopt_create expects in weights_host for this configuration, 0 if the
@@ -125,12 +137,10 @@ size_t lopt_weights_count(const lopt_config* cfg);
  * Errors: LOPT_EINVAL (null, struct_size, hidden/lstm_hidden/n_bank out of range, decay
  * outside [0,1), negative eps), LOPT_ESTATE (n_weights != lopt_weights_count), LOPT_ENOMEM,
  * LOPT_EHIP.
- * Tuning knobs read from the environment here (none changes what is computed beyond rounding):
- *   LOPT_APPLY = auto | valu | mfma_f32 | mfma_f16x3 | mfma_f16s   apply kernel for hidden width 32
- *                (auto = mfma_f16s: split-fp16 matrix cores, column strips, software-pipelined)
- *   LOPT_GROUPS = 0..16   number of tensor groups of the two-stream pipeline (0 = by list size;
- *                1 = every pass over the whole list, one after the other, on the caller's stream)
- * Any other value of either is refused with LOPT_EINVAL. */
+ * Kernel and launch-plan selection is per context: cfg->apply_kernel and cfg->groups. Where a field is 0
+ * (automatic), the environment may set it for experiments without touching the caller's code:
+ *   LOPT_APPLY = auto | valu | mfma_f32 | mfma_f16s        LOPT_GROUPS = 0..16
+ * Any other value of either, in the field or in the environment, is refused with LOPT_EINVAL. */
 lopt_status lopt_create(const lopt_config* cfg, const float* weights_host, size_t n_weights,
                         lopt_ctx** out);
 

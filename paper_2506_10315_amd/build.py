@@ -19,7 +19,6 @@ UNITS = [
     ("lopt_apply_valu.hip", "apply_small_fc", ["-DLOPT_APPLY_KIND=0"]),
     ("lopt_apply_valu.hip", "apply_velo", ["-DLOPT_APPLY_KIND=1"]),
     ("lopt_apply_mfma.hip", "apply_mfma", []),
-    ("lopt_apply_f16.hip", "apply_f16", []),
     ("lopt_apply_f16s.hip", "apply_f16s", []),
     ("lopt_apply_velo4.hip", "apply_velo4", []),
 ]

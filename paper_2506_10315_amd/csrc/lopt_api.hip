@@ -55,6 +55,8 @@ bool config_ok(const lopt_config* c, std::string* why) {
     if (!(v >= 0.f && v < 1.f)) return bad("every decay must be in [0, 1)");
   if (!(c->eps_acc >= 0.f) || !(c->eps_norm >= 0.f)) return bad("eps_acc and eps_norm must be >= 0");
   if (!std::isfinite(c->exp_mult) || !std::isfinite(c->step_mult)) return bad("exp_mult/step_mult must be finite");
+  if (c->apply_kernel > LOPT_APPLY_MFMA_F16S) return bad("config.apply_kernel is not a lopt_apply_kernel");
+  if (c->groups > (uint32_t)kMaxGroups) return bad("config.groups must be in [0, 16]");
   if (c->kind == LOPT_VELO) {
     if (c->lstm_hidden < 1 || c->lstm_hidden > 1024) return bad("config.lstm_hidden must be in [1, 1024]");
     if (c->n_bank < 1 || c->n_bank > 1024) return bad("config.n_bank must be in [1, 1024]");
@@ -160,10 +162,10 @@ struct lopt_ctx {
   size_t h_stage_bytes = 0;
   hipEvent_t stage_ev = nullptr;
   bool stage_pending = false;
-  int apply_variant = 0;           // 0 auto, 1 vector ALU, 2 fp32 MFMA, 3 split-fp16 MFMA row form, 4 strip form (LOPT_APPLY in the environment at create)
+  int apply_variant = 0;           // lopt_apply_kernel (configuration field, else LOPT_APPLY in the environment at create)
   // Group pipeline (small_fc_lopt, strip-form apply): the tensor list is cut into groups; the HBM-bound passes of
   // group g+1 run on `aux_stream` while the compute-bound apply pass of group g runs on the caller's stream.
-  int groups_override = 0;         // LOPT_GROUPS in the environment at create (0 = choose by size)
+  int groups_override = 0;         // configuration field, else LOPT_GROUPS in the environment at create (0 = choose by size)
   hipStream_t aux_stream = nullptr;
   hipEvent_t ev_fork = nullptr;
   std::vector<hipEvent_t> ev_start, ev_pre;   // per group: "previous group's passes are enqueued" / "this group's passes are done"
@@ -484,19 +486,21 @@ lopt_status lopt_create(const lopt_config* cfg, const float* weights_host, size_
     try { eq = equilibrate_small_fc(weights_host, (int)cfg->hidden); } catch (const std::bad_alloc&) { return fail(nullptr, LOPT_ENOMEM, "out of host memory"); }
     weights_host = eq.data();   // from here on: the equivalent, rescaled network
   }
-  int apply_variant = 0, groups_override = 0;
+  // the configuration's fields select kernel and launch plan; the environment fills in fields left at 0
+  int apply_variant = (int)cfg->apply_kernel, groups_override = (int)cfg->groups;
   if (const char* e = getenv("LOPT_APPLY")) {
-    apply_variant = !strcmp(e, "auto") ? 0 : !strcmp(e, "valu") ? 1 : !strcmp(e, "mfma_f32") ? 2 : !strcmp(e, "mfma_f16x3") ? 3
-                  : !strcmp(e, "mfma_f16s") ? 4 : -1;
-    if (apply_variant < 0)
-      return fail(nullptr, LOPT_EINVAL, std::string("LOPT_APPLY=") + e + " is not one of auto, valu, mfma_f32, mfma_f16x3, mfma_f16s");
+    const int v = !strcmp(e, "auto") ? LOPT_APPLY_AUTO : !strcmp(e, "valu") ? LOPT_APPLY_VALU
+                : !strcmp(e, "mfma_f32") ? LOPT_APPLY_MFMA_F32 : !strcmp(e, "mfma_f16s") ? LOPT_APPLY_MFMA_F16S : -1;
+    if (v < 0)
+      return fail(nullptr, LOPT_EINVAL, std::string("LOPT_APPLY=") + e + " is not one of auto, valu, mfma_f32, mfma_f16s");
+    if (!apply_variant) apply_variant = v;
   }
   if (const char* e = getenv("LOPT_GROUPS")) {
     char* end = nullptr;
     const long g = strtol(e, &end, 10);
     if (end == e || *end || g < 0 || g > kMaxGroups)
       return fail(nullptr, LOPT_EINVAL, std::string("LOPT_GROUPS=") + e + " is not an integer in [0, 16]");
-    groups_override = (int)g;
+    if (!groups_override) groups_override = (int)g;
   }
   lopt_ctx* ctx = new (std::nothrow) lopt_ctx();
   if (!ctx) return fail(nullptr, LOPT_ENOMEM, "out of host memory");
@@ -731,16 +735,15 @@ static lopt_status step_impl(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* de
   const bool profiling = ctx->profiling && !use_static;   // per-pass timing creates events: not on the static path
   StepArgs A = make_args(ctx, step, lr, weight_decay, (int)n);
   const bool mfma_ok = apply_mfma_available(A);
-  // the strip-form kernel addresses a row pair with 32-bit byte offsets
-  bool strip_ok = mfma_ok && (ctx->apply_variant == 0 || ctx->apply_variant == 4);
-  for (size_t i = 0; strip_ok && i < n; ++i) strip_ok = descs[i].cols < (1 << 28);
+  // the strip-form kernel addresses a row pair with 32-bit byte offsets from the tile's first column: 4 (127 + cols)
+  // must fit, which only a tensor of two rows and 2^30 - 127 or more columns breaks (it takes the fp32 kernel)
+  bool strip_ok = mfma_ok && (ctx->apply_variant == LOPT_APPLY_AUTO || ctx->apply_variant == LOPT_APPLY_MFMA_F16S);
+  for (size_t i = 0; strip_ok && i < n; ++i) strip_ok = descs[i].rows == 1 || descs[i].cols <= (1 << 30) - 128;
   auto launch_apply = [&](const Launch& La) {
     if (strip_ok) launch_apply_f16s(La, A, ctx->W, stream);
-    else if (mfma_ok && (ctx->apply_variant == 0 || ctx->apply_variant == 3 || ctx->apply_variant == 4))
-      launch_apply_f16x3(La, A, ctx->W, stream);
-    else if (mfma_ok && ctx->apply_variant == 2) launch_apply_mfma(La, A, ctx->W, stream);
+    else if (mfma_ok && ctx->apply_variant != LOPT_APPLY_VALU) launch_apply_mfma(La, A, ctx->W, stream);
     else if (ctx->cfg.kind == LOPT_SMALL_FC) launch_apply_small_fc(La, A, ctx->W, stream);
-    else if (ctx->apply_variant != 1 && apply_velo4_available(A)) launch_apply_velo4(La, A, stream);
+    else if (ctx->apply_variant != LOPT_APPLY_VALU && apply_velo4_available(A)) launch_apply_velo4(La, A, stream);
     else launch_apply_velo(La, A, ctx->W, stream);
   };
   // ---- group pipeline: only where the apply pass is compute-bound (strip form), the list is large enough to

@@ -2,9 +2,27 @@
 // hidden width 32 (paper: "Kernel 2: fused feature construction and network application"; its H100
 // appendix puts the MLP contraction on tensor cores).
 //
-// Arithmetic: as in the row form (lopt_apply_f16.hip). Every operand of the two hidden-layer contractions
-// is an unevaluated sum of two fp16 numbers, x = hi + lo, and a product keeps hi*Whi + lo*Whi + hi*Wlo with
-// fp32 accumulation on v_mfma_f32_32x32x16_f16; features are normalized before the contraction.
+// Why not the fp32 MFMA: on gfx950 v_mfma_f32_32x32x2_f32 runs at the rate of the vector FP32 lanes and does not
+// overlap with vector-ALU work of the same SIMD (measured: time = MFMA time + VALU time), while the 16-bit MFMAs run
+// on the matrix engine at 16x the rate and DO overlap with the vector ALU. So the two hidden-layer contractions are
+// done in fp16 with fp32 accumulation, and every operand is carried as an unevaluated sum of two fp16 numbers,
+// x = hi + lo with hi = fp16_rtz(x) and lo = fp16_rtz(x - hi): 22 significand bits. A product keeps the three
+// leading terms
+//   x*w = hi*Whi + lo*Whi + hi*Wlo            (the dropped lo*Wlo is below 2^-22 relative)
+// i.e. three v_mfma_f32_32x32x16_f16 per 16 values of k. Accuracy is that of fp32 arithmetic to within a small factor;
+// the range is fp16's, which is why features are normalized BEFORE the contraction (normalized features are bounded by
+// sqrt(N) < 46341 < 65504) instead of folding the normalization into W1, and why lopt_create rescales the hidden
+// units by powers of two (no pre-activation can leave the range).
+//
+// Layout: products are computed transposed, D[unit, element] = W^T[unit, k] X^T[k, element]. One MFMA takes 16 values
+// of k: lanes 0..31 hold k 0..7 of element (lane & 31) as four packed registers, lanes 32..63 hold k 8..15 of the same
+// element.
+//   * layer 1 (k = the 16 per-element features): each lane packs its own element's features into 8 registers (hi) + 8
+//     (lo); v_permlane32_swap of register i with register 4+i yields the B operands of the wave's two 32-element tiles.
+//   * the accumulator leaves lane l with 16 hidden units of element (l & 31): registers 0..7 are k 0..7 of layer 2's
+//     first MFMA for this lane half, registers 8..15 those of its second MFMA; ReLU, split and pack happen in place,
+//     no cross-lane traffic. The weights are packed per lane in that order.
+//   * layer 3 and the update: vector ALU, fp32.
 //
 // Ownership (what makes the kernel small in registers and in vector-ALU work):
 //   * A wavefront owns a strip of 32 columns and sweeps its rows two at a time: lane (h, c) holds the
@@ -194,7 +212,7 @@ __global__ void __launch_bounds__(kBlock, 2) k_apply_f16s(const TensorDev* __res
   Consts C;
   C.eps = A.eps_acc; C.lr = A.lr; C.wd = A.wd; C.exp_mult = A.exp_mult; C.step_mult = A.step_mult;
   C.b3d = tail[kH * kH + kH + 2 * kH]; C.b3m = tail[kH * kH + kH + 2 * kH + 1];
-  // ---- weights of this lane, split and packed (the same packing as the row form)
+  // ---- weights of this lane, split and packed in the order the accumulator layout asks for
   {
     const float* __restrict__ w1raw = tail + (kH * kH + kH + 2 * kH + 2 + 2);  // W1[28][32], not normalized
     unsigned ph[4], pl[4];
@@ -309,14 +327,16 @@ __global__ void __launch_bounds__(kBlock, 2) k_apply_f16s(const TensorDev* __res
   S.g = (gcf32)T.g; S.p = (gcf32)T.p;
   S.m1 = (gcf32)T.st; S.m2 = S.m1 + T.padN; S.m3 = S.m2 + T.padN; S.v = S.m3 + T.padN;
   const gf32 pout = (gf32)T.p;
-  // lane offsets in bytes (the host keeps tensors with 8 * cols >= 2^32 away from this kernel)
-  const unsigned colc_ = 4u * (unsigned)(col_ok ? col : n - 1);
+  // lane offsets in bytes, relative to the tile's first column (which goes into the wave-uniform row offset): at most
+  // 4 (127 + n) with n < 2^30 whenever a tensor has a second row, so 32 bits hold them for every legal shape
+  const size_t c0 = (size_t)at.c0;
+  const unsigned colc_ = 4u * (unsigned)((col_ok ? col : n - 1) - at.c0);
   const unsigned voff_pair = colc_ + (half ? 4u * (unsigned)n : 0u);
   // the pipeline's run-out rounds (q >= r1) read the tile's last row once more: a cache hit, not HBM traffic
   auto fetch = [&](int q) __attribute__((always_inline)) {
     const bool in_tile = q < r1;
     const int qc = in_tile ? q : r1 - 1;
-    return load_elem(S, (size_t)qc * (size_t)n, in_tile && qc + 1 < m ? voff_pair : colc_);
+    return load_elem(S, (size_t)qc * (size_t)n + c0, in_tile && qc + 1 < m ? voff_pair : colc_);
   };
 
   // One step of the pipeline. On entry: h2a/h2b/p_e belong to the round of rows qe, qe+1 (layer 3 and update
@@ -378,7 +398,7 @@ __global__ void __launch_bounds__(kBlock, 2) k_apply_f16s(const TensorDev* __res
       const float delta = d * __expf(mg * C.exp_mult) * C.step_mult;
       if (col_ok && qe + half < r1)
         __builtin_nontemporal_store(p_e - C.lr * (delta + C.wd * p_e),
-                                    (gf32)((gc8)(pout + (size_t)qe * (size_t)n) + voff_pair));
+                                    (gf32)((gc8)(pout + ((size_t)qe * (size_t)n + c0)) + voff_pair));
     }
     p_e = p_n;
     LOPT_SB();

@@ -112,7 +112,6 @@ bool apply_mfma_available(const StepArgs&);
 void launch_apply_mfma(const Launch&, const StepArgs&, const WeightsDev&, hipStream_t);
 bool apply_velo4_available(const StepArgs&);
 void launch_apply_velo4(const Launch&, const StepArgs&, hipStream_t);
-void launch_apply_f16x3(const Launch&, const StepArgs&, const WeightsDev&, hipStream_t);
 void launch_apply_f16s(const Launch&, const StepArgs&, const WeightsDev&, hipStream_t);
 
 }  // namespace lopt

@@ -120,6 +120,12 @@ def test_create_refuses_unknown_tuning_knob_values_and_non_finite_weights(monkey
     wp = w.ctypes.data_as(C.POINTER(C.c_float))
     ctx = C.c_void_p()
     c = P.default_config(0)
+    c.apply_kernel = 4
+    assert L.lopt_create(C.byref(c), wp, 2402, C.byref(ctx)) == 1 and b"apply_kernel" in L.lopt_last_error(None)
+    c = P.default_config(0)
+    c.groups = 17
+    assert L.lopt_create(C.byref(c), wp, 2402, C.byref(ctx)) == 1 and b"groups" in L.lopt_last_error(None)
+    c = P.default_config(0)
     monkeypatch.setenv("LOPT_APPLY", "mfma_f16")            # a misspelt variant must not silently mean "auto"
     assert L.lopt_create(C.byref(c), wp, 2402, C.byref(ctx)) == 1 and b"LOPT_APPLY" in L.lopt_last_error(None)
     monkeypatch.delenv("LOPT_APPLY")

@@ -49,6 +49,29 @@ def test_two_runs_are_bit_identical(kind):
         assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
 
 
+def test_groups_field_of_the_configuration_selects_the_plan_per_context():
+    # two contexts in one process, one with every pass over the whole list on one stream, one with three tensor groups
+    # on two streams: same bits (the selection is per context, no environment involved)
+    import torch
+    import paper_2506_10315_amd as P
+    outs = []
+    for groups in (1, 3):
+        cfg = Hn.make_cfg("small_fc_lopt", groups=groups)
+        w = Hn.random_weights(cfg, 0)
+        specs = [W.TensorSpec(f"t{i}", s) for i, s in enumerate(SHAPES)]
+        case = Hn.Case(201, specs, "gauss_logscale")
+        opt = P.LearnedOptimizer(cfg, w, SHAPES)
+        p = [torch.from_numpy(case.p0(i)).to("cuda:0") for i in range(len(specs))]
+        for t in range(3):
+            g = [torch.from_numpy(case.grad(i, t)).to("cuda:0") for i in range(len(specs))]
+            opt.step(p, g, lr=0.7, weight_decay=0.01, step=t)
+        torch.cuda.synchronize()
+        outs.append([x.cpu().numpy().copy() for x in p] + [x.cpu().numpy().copy() for x in opt.state])
+        opt.close()
+    for x, y in zip(*outs):
+        assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
+
+
 @pytest.mark.parametrize("groups", [2, 3, 16])
 def test_group_pipeline_is_bit_identical_to_one_stream(groups, monkeypatch):
     # LOPT_GROUPS (read when the context is created) cuts the list into tensor groups whose HBM-bound passes run on

@@ -163,8 +163,8 @@ def test_maximum_size_tensor_matches_its_periodic_base_pattern(kind, capsys):
 
 
 def test_widest_tensor_matches_its_periodic_base_pattern(capsys):
-    # 4 x 2^28: a million column tiles per pass, and the width from which the strip-form apply kernel (32-bit byte
-    # offsets inside a row pair) hands the list to the row-form kernel
+    # 4 x 2^28: a million column tiles per pass; the strip-form apply kernel's 32-bit lane offsets (relative to the
+    # tile's first column) at 4 GiB per row
     _periodic_tensor_case("small_fc_lopt", 1, 1 << 26, _progress(capsys), "widest")
 
 
