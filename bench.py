@@ -29,20 +29,35 @@ MFMA_F16_PEAK_TFLOPS = 2500.0     # dense fp16/bf16 matrix peak
 
 # Algorithmic work per element of the streaming passes:
 #   apply pass, small_fc_lopt hidden 32: MLP contraction 28*32 + 32*32 + 32*2 MACs = 3968 FLOP
-#   apply pass bytes: read g, p, M1..3, V (24 B) + write p (4 B) = 28 B
-#   accum_stats pass bytes: read g, p, M1..3, V (24 B) + write M1..3, V (16 B) = 40 B;  rowcol_sums: read g = 4 B
+#   rowcol_sums: read g = 4 B. The pass that writes the new M1..3, V reads g, p, M1..3, V (24 B) and writes 16 B more:
+#     state written by accum_stats (LOPT_STATE_PASS=stats, or an apply kernel other than the two default ones):
+#       accum_stats 24 + 16 = 40 B, apply 24 + 4 (write p) = 28 B
+#     state written by the apply pass (k_apply_f16s and k_apply_velo4, the default): accum_stats 24 B, apply 24 + 20 = 44 B
 #   whole step: 44 B compulsory (24 read + 20 written), 72 B when the three dependent sweeps all go to HBM
 APPLY_FLOP_SMALL_FC = 2 * (28 * 32 + 32 * 32 + 32 * 2)
-PASS_BYTES = {"rowcol_sums": 4, "accum_stats": 40, "apply": 28}
+
+
+def state_in_apply(apply_kernel):
+    return apply_kernel in ("k_apply_f16s", "k_apply_velo4") and os.environ.get("LOPT_STATE_PASS", "auto") != "stats"
+
+
+def pass_bytes(apply_kernel):
+    in_apply = state_in_apply(apply_kernel)
+    return {"rowcol_sums": 4, "accum_stats": 24 if in_apply else 40, "apply": 44 if in_apply else 28}
+
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by what the same counters read
-# for a plain 256 MiB copy: 2.0 and 1.0), keyed by (element count of the list, kernel). A kernel or list that was
-# not profiled reports null. Source: profiles/hbm_traffic_vit_b16.md.
+# for a plain 256 MiB copy: 2.0 and 1.0), keyed by (element count of the list, kernel, pass that writes the
+# accumulators). A kernel or list that was not profiled reports null. Source: profiles/hbm_traffic_vit_b16.md.
 MEASURED_TRAFFIC_BYTES = {
-    (86_567_656, "k_apply_f16s"): (1_044_874 * 2.0 + 338_455) * 1024,
-    (86_567_656, "k_apply_velo4"): (1_024_085 * 2.0 + 338_155) * 1024,
-    (86_567_656, "k_accum_stats"): (1_020_449 * 2.0 + 1_353_160) * 1024,
-    (86_567_656, "k_rowcol_sums"): (169_589 * 2.0 + 7_108) * 1024,
+    (86_567_656, "k_apply_f16s", "apply"): (1_048_339 * 2.0 + 1_691_076) * 1024,
+    (86_567_656, "k_apply_velo4", "apply"): (1_024_092 * 2.0 + 1_690_784) * 1024,
+    (86_567_656, "k_accum_stats", "apply"): (1_019_353 * 2.0 + 540) * 1024,
+    (86_567_656, "k_rowcol_sums", "apply"): (169_592 * 2.0 + 7_108) * 1024,
+    (86_567_656, "k_apply_f16s", "stats"): (1_044_874 * 2.0 + 338_455) * 1024,
+    (86_567_656, "k_apply_velo4", "stats"): (1_024_085 * 2.0 + 338_155) * 1024,
+    (86_567_656, "k_accum_stats", "stats"): (1_020_449 * 2.0 + 1_353_160) * 1024,
+    (86_567_656, "k_rowcol_sums", "stats"): (169_589 * 2.0 + 7_108) * 1024,
 }
 
 APPLY_KERNEL = {"auto": "k_apply_f16s", "mfma_f16s": "k_apply_f16s", "mfma_f32": "k_apply_mfma", "valu": "k_apply"}
@@ -172,10 +187,9 @@ def measure(wl, config_id, steps, warmup, device_draws=False, graph=False):
     dominant = max(pass_ms, key=pass_ms.get)
     dur_s = pass_ms[dominant] * 1e-3
     variant = os.environ.get("LOPT_APPLY", "auto")
-    if dominant == "apply":
-        kernel = APPLY_KERNEL[variant] if optimizer == "small_fc_lopt" else ("k_apply_velo4" if variant != "valu" else "k_apply")
-    else:
-        kernel = "k_" + dominant
+    apply_kernel = APPLY_KERNEL[variant] if optimizer == "small_fc_lopt" else ("k_apply_velo4" if variant != "valu" else "k_apply")
+    kernel = apply_kernel if dominant == "apply" else "k_" + dominant
+    PASS_BYTES = pass_bytes(apply_kernel)
     # the two roofs of that kernel: HBM at its algorithmic bytes, and (for the MLP contraction on the matrix cores) the
     # dense peak of the operand type the contraction runs in; the one that allows less is the bound
     hbm_gbs = PASS_BYTES.get(dominant, 0) * n_el / dur_s / 1e9
@@ -193,13 +207,14 @@ def measure(wl, config_id, steps, warmup, device_draws=False, graph=False):
             "hbm": {"algorithmic_bytes_per_element": PASS_BYTES["apply"], "achieved_GBs": hbm_gbs, "frac": hbm_gbs / HBM_PEAK_GBS},
             "mfma": {"algorithmic_flop_per_element": APPLY_FLOP_SMALL_FC, "operand_dtype_peak_TFLOPs": peak_tf,
                      "achieved_TFLOPs": tflops, "frac": tflops / peak_tf},
-            "note": "arithmetic intensity 3968 FLOP / 28 B = 142 FLOP/B; the ridge of the fp16 matrix roof is 312 FLOP/B, "
+            "note": f"arithmetic intensity 3968 FLOP / {PASS_BYTES['apply']} B = {APPLY_FLOP_SMALL_FC / PASS_BYTES['apply']:.0f} FLOP/B; the ridge of the fp16 matrix roof is 312 FLOP/B, "
                     "so with the contraction on the fp16 matrix cores the HBM roof is the lower one; what occupies the "
                     "kernel in fact is vector-instruction issue (operand splits, ReLU, layer 3): profiles/sq_counters_vit_b16.md"}
         roofline["contraction"] = APPLY_ARITH[kernel]
     else:
         roofline.update(bound="hbm", achieved=hbm_gbs, peak=HBM_PEAK_GBS, unit="GB/s", frac=hbm_gbs / HBM_PEAK_GBS)
-    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get((n_el, kernel))
+    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get((n_el, kernel, "apply" if state_in_apply(apply_kernel) else "stats"))
+    roofline["state_written_by"] = "apply pass" if state_in_apply(apply_kernel) else "statistics pass"
     roofline["traffic_unit"] = "HBM bytes per launch of this kernel on this list (rocprofv3 FETCH_SIZE x2 + WRITE_SIZE, profiles/); null = not profiled"
     roofline["pass_ms"] = pass_ms
     roofline["ms_per_step_with_events"] = dt_prof / steps * 1e3
@@ -214,8 +229,7 @@ def measure(wl, config_id, steps, warmup, device_draws=False, graph=False):
                                "while events are on)")
     res = {"optimizer": optimizer, "n_tensors": n, "n_elements": n_el, "ms_per_step": per_step_s * 1e3,
            "value": n_el / per_step_s / 1e9, "settle_steps": settle, "finite": finite, "roofline": roofline,
-           "hidden": int(cfg.hidden), "dtype": dtype_of(optimizer, kernel if dominant == "apply" else
-                                                        (APPLY_KERNEL[variant] if optimizer == "small_fc_lopt" else "k_apply_velo4"))}
+           "hidden": int(cfg.hidden), "dtype": dtype_of(optimizer, apply_kernel)}
     if graph_info:
         res["graph"] = graph_info
     return res

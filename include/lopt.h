@@ -76,6 +76,18 @@ typedef enum {
   LOPT_APPLY_MFMA_F16S = 3  /* matrix cores on fp16 hi+lo operand pairs, fp32 accumulate; column strips, software-pipelined */
 } lopt_apply_kernel;
 
+/* Which pass writes the new momentum / second-moment accumulators M_1..3, V when the apply kernel is one of the two
+ * default ones: LOPT_APPLY_MFMA_F16S (small_fc_lopt, hidden 32) or the width-4 VeLO kernel. Every other kernel
+ * combination writes them in the statistics pass. The values are the same bit for bit either way: both passes form
+ * them with the same fp32 operations from the same inputs. */
+typedef enum {
+  LOPT_STATE_AUTO = 0,      /* = LOPT_STATE_IN_APPLY */
+  LOPT_STATE_IN_STATS = 1,  /* statistics pass reads and writes them (40 bytes per element), apply pass reads them (28) */
+  LOPT_STATE_IN_APPLY = 2   /* statistics pass only reads them (24 bytes per element, and a read-only stream reaches a
+                               higher share of the HBM rate than a read-write one); the apply pass forms them again and
+                               writes them (44 bytes per element) */
+} lopt_state_pass;
+
 /* Number of time features tanh(t/x), x in {1,3,10,30,100,300,1e3,3e3,1e4,3e4,1e5}
  * (feature table of small_fc_lopt, row "Time Features"). */
 #define LOPT_N_TIME 11
@@ -109,6 +121,7 @@ typedef struct {
   uint32_t apply_kernel; /* lopt_apply_kernel; 0 = automatic */
   uint32_t groups;      /* tensor groups of the two-stream pipeline, 1..16 (1 = every pass over the whole list, one after
                            the other, on the caller's stream); 0 = by list size */
+  uint32_t state_pass;  /* lopt_state_pass; 0 = automatic */
 } lopt_config;
 
 typedef struct {
@@ -119,7 +132,7 @@ typedef struct {
 
 /* Fill *cfg with the defaults for `kind`: decays {0.9,0.99,0.999}, 0.999, {0.9,0.99,0.999};
  * eps_acc 1e-16; eps_norm 1e-30; alpha = beta = 0.01; hidden 32 (small_fc_lopt) or 4 (VeLO);
- * lstm_hidden 512, n_bank 256; apply_kernel and groups automatic. Returns LOPT_EINVAL for a null cfg or unknown kind. */
+ * lstm_hidden 512, n_bank 256; apply_kernel, groups and state_pass automatic. Returns LOPT_EINVAL for a null cfg or unknown kind. */
 lopt_status lopt_default_config(uint32_t kind, lopt_config* cfg);
 
 /* Number of floats lopt_create expects in weights_host for this configuration, 0 if the
@@ -137,10 +150,10 @@ size_t lopt_weights_count(const lopt_config* cfg);
  * Errors: LOPT_EINVAL (null, struct_size, hidden/lstm_hidden/n_bank out of range, decay
  * outside [0,1), negative eps), LOPT_ESTATE (n_weights != lopt_weights_count), LOPT_ENOMEM,
  * LOPT_EHIP.
- * Kernel and launch-plan selection is per context: cfg->apply_kernel and cfg->groups. Where a field is 0
- * (automatic), the environment may set it for experiments without touching the caller's code:
- *   LOPT_APPLY = auto | valu | mfma_f32 | mfma_f16s        LOPT_GROUPS = 0..16
- * Any other value of either, in the field or in the environment, is refused with LOPT_EINVAL. */
+ * Kernel and launch-plan selection is per context: cfg->apply_kernel, cfg->groups and cfg->state_pass. Where a field
+ * is 0 (automatic), the environment may set it for experiments without touching the caller's code:
+ *   LOPT_APPLY = auto | valu | mfma_f32 | mfma_f16s     LOPT_GROUPS = 0..16     LOPT_STATE_PASS = auto | stats | apply
+ * Any other value of these, in the field or in the environment, is refused with LOPT_EINVAL. */
 lopt_status lopt_create(const lopt_config* cfg, const float* weights_host, size_t n_weights,
                         lopt_ctx** out);
 

@@ -11,6 +11,7 @@ _LIB_PATH = os.environ.get("LOPT_LIB_PATH") or os.path.join(_HERE, "liblopt.so")
 LOPT_SMALL_FC = 0
 LOPT_VELO = 1
 APPLY_KERNELS = {"auto": 0, "valu": 1, "mfma_f32": 2, "mfma_f16s": 3}   # lopt_apply_kernel
+STATE_PASSES = {"auto": 0, "stats": 1, "apply": 2}                        # lopt_state_pass
 N_PASSES = 7
 _STATUS = {0: "LOPT_OK", 1: "LOPT_EINVAL", 2: "LOPT_ESHAPE", 3: "LOPT_ESTATE", 4: "LOPT_ENOMEM", 5: "LOPT_EHIP",
            6: "LOPT_ELIMIT"}
@@ -33,7 +34,7 @@ class lopt_config(C.Structure):
                 ("mom_decay", C.c_float * 3), ("rms_decay", C.c_float), ("fac_decay", C.c_float * 3),
                 ("eps_acc", C.c_float), ("eps_norm", C.c_float), ("exp_mult", C.c_float),
                 ("step_mult", C.c_float), ("lstm_hidden", C.c_uint32), ("n_bank", C.c_uint32),
-                ("apply_kernel", C.c_uint32), ("groups", C.c_uint32)]
+                ("apply_kernel", C.c_uint32), ("groups", C.c_uint32), ("state_pass", C.c_uint32)]
 
 
 class lopt_tensor_desc(C.Structure):

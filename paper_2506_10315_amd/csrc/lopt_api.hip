@@ -57,6 +57,7 @@ bool config_ok(const lopt_config* c, std::string* why) {
   if (!std::isfinite(c->exp_mult) || !std::isfinite(c->step_mult)) return bad("exp_mult/step_mult must be finite");
   if (c->apply_kernel > LOPT_APPLY_MFMA_F16S) return bad("config.apply_kernel is not a lopt_apply_kernel");
   if (c->groups > (uint32_t)kMaxGroups) return bad("config.groups must be in [0, 16]");
+  if (c->state_pass > LOPT_STATE_IN_APPLY) return bad("config.state_pass is not a lopt_state_pass");
   if (c->kind == LOPT_VELO) {
     if (c->lstm_hidden < 1 || c->lstm_hidden > 1024) return bad("config.lstm_hidden must be in [1, 1024]");
     if (c->n_bank < 1 || c->n_bank > 1024) return bad("config.n_bank must be in [1, 1024]");
@@ -154,6 +155,7 @@ struct lopt_ctx {
   Plan plan;
   bool plan_valid = false;
   TableStore heap, fixed;
+  bool state_in_apply = true;      // the strip-form apply kernel writes M_1..3, V (configuration field state_pass)
   bool failed = false;             // a HIP call failed in the middle of a launch sequence: the context refuses further steps
   float loss = 0.f;                // lopt_set_loss: goes with the gradients of the following steps (VeLO)
   uint64_t id = 0;                 // names this context as the owner of the static scratch's contents
@@ -487,7 +489,7 @@ lopt_status lopt_create(const lopt_config* cfg, const float* weights_host, size_
     weights_host = eq.data();   // from here on: the equivalent, rescaled network
   }
   // the configuration's fields select kernel and launch plan; the environment fills in fields left at 0
-  int apply_variant = (int)cfg->apply_kernel, groups_override = (int)cfg->groups;
+  int apply_variant = (int)cfg->apply_kernel, groups_override = (int)cfg->groups, state_pass = (int)cfg->state_pass;
   if (const char* e = getenv("LOPT_APPLY")) {
     const int v = !strcmp(e, "auto") ? LOPT_APPLY_AUTO : !strcmp(e, "valu") ? LOPT_APPLY_VALU
                 : !strcmp(e, "mfma_f32") ? LOPT_APPLY_MFMA_F32 : !strcmp(e, "mfma_f16s") ? LOPT_APPLY_MFMA_F16S : -1;
@@ -502,10 +504,17 @@ lopt_status lopt_create(const lopt_config* cfg, const float* weights_host, size_
       return fail(nullptr, LOPT_EINVAL, std::string("LOPT_GROUPS=") + e + " is not an integer in [0, 16]");
     if (!groups_override) groups_override = (int)g;
   }
+  if (const char* e = getenv("LOPT_STATE_PASS")) {
+    const int v = !strcmp(e, "auto") ? LOPT_STATE_AUTO : !strcmp(e, "stats") ? LOPT_STATE_IN_STATS
+                : !strcmp(e, "apply") ? LOPT_STATE_IN_APPLY : -1;
+    if (v < 0) return fail(nullptr, LOPT_EINVAL, std::string("LOPT_STATE_PASS=") + e + " is not one of auto, stats, apply");
+    if (!state_pass) state_pass = v;
+  }
   lopt_ctx* ctx = new (std::nothrow) lopt_ctx();
   if (!ctx) return fail(nullptr, LOPT_ENOMEM, "out of host memory");
   ctx->cfg = *cfg;
   ctx->apply_variant = apply_variant;
+  ctx->state_in_apply = state_pass != LOPT_STATE_IN_STATS;
   ctx->groups_override = groups_override;
   const int H = (int)cfg->hidden;
   ctx->HP = padded_hidden(H);
@@ -736,14 +745,22 @@ static lopt_status step_impl(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* de
   StepArgs A = make_args(ctx, step, lr, weight_decay, (int)n);
   const bool mfma_ok = apply_mfma_available(A);
   // the strip-form kernel addresses a row pair with 32-bit byte offsets from the tile's first column: 4 (127 + cols)
-  // must fit, which only a tensor of two rows and 2^30 - 127 or more columns breaks (it takes the fp32 kernel)
+  // must stay below the range of its store descriptors (2^32 - 512), which only a tensor of two or more rows and
+  // 2^30 - 255 or more columns breaks (it takes the fp32 kernel)
   bool strip_ok = mfma_ok && (ctx->apply_variant == LOPT_APPLY_AUTO || ctx->apply_variant == LOPT_APPLY_MFMA_F16S);
-  for (size_t i = 0; strip_ok && i < n; ++i) strip_ok = descs[i].rows == 1 || descs[i].cols <= (1 << 30) - 128;
+  for (size_t i = 0; strip_ok && i < n; ++i) strip_ok = descs[i].rows == 1 || descs[i].cols <= (1 << 30) - 256;
+  // With the two default apply kernels the momentum / second-moment accumulators are written by the apply pass and the
+  // statistics pass only reads them: 24 + 44 instead of 40 + 28 bytes per element (configuration field state_pass).
+  // The read-only statistics stream runs at 83 % of the HBM rate against 67 % for the read-write one; the strip-form
+  // kernel is bound by instruction issue and takes the extra stores in its stride, the VeLO kernel is HBM-bound and
+  // gives part of the gain back.
+  const bool velo4_ok = ctx->cfg.kind == LOPT_VELO && ctx->apply_variant != LOPT_APPLY_VALU && apply_velo4_available(A);
+  const bool state_in_apply = (strip_ok || velo4_ok) && ctx->state_in_apply;
   auto launch_apply = [&](const Launch& La) {
-    if (strip_ok) launch_apply_f16s(La, A, ctx->W, stream);
+    if (strip_ok) launch_apply_f16s(La, A, ctx->W, state_in_apply, stream);
     else if (mfma_ok && ctx->apply_variant != LOPT_APPLY_VALU) launch_apply_mfma(La, A, ctx->W, stream);
     else if (ctx->cfg.kind == LOPT_SMALL_FC) launch_apply_small_fc(La, A, ctx->W, stream);
-    else if (ctx->apply_variant != LOPT_APPLY_VALU && apply_velo4_available(A)) launch_apply_velo4(La, A, stream);
+    else if (velo4_ok) launch_apply_velo4(La, A, state_in_apply, stream);
     else launch_apply_velo(La, A, ctx->W, stream);
   };
   // ---- group pipeline: only where the apply pass is compute-bound (strip form), the list is large enough to
@@ -791,7 +808,7 @@ static lopt_status step_impl(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* de
     };
     // accumulator update + statistics + per-tensor finalize of one group: what its apply pass waits for
     auto stats_passes = [&](const Launch& S, hipStream_t s) {
-      launch_accum_stats(S, A, s);
+      launch_accum_stats(S, A, !state_in_apply, s);
       launch_finalize(S, A, ctx->W, ws + pl.oLstmU, s);
       if (velo) {
         launch_velo_lstm(S, A, ctx->W, ws + pl.oLstmU, ws + pl.oBeff, ws + pl.oHNew, s);
@@ -839,7 +856,7 @@ static lopt_status step_impl(lopt_ctx* ctx, size_t n, const lopt_tensor_desc* de
   MARK(1);
   launch_rc_update(L, A, ctx->W, ws + pl.oHbarPart, ws + pl.oBeff, stream);
   MARK(2);
-  launch_accum_stats(L, A, stream);
+  launch_accum_stats(L, A, !state_in_apply, stream);
   MARK(3);
   launch_finalize(L, A, ctx->W, ws + pl.oLstmU, stream);
   MARK(4);

@@ -141,6 +141,7 @@ struct Consts {
   float sc[10];                     // normalization factors of features 0..9 (wave-uniform)
   f16x8 b_one_lo, b_one_hi;         // B operands selecting k slots (0, 1) of the lower / upper lane half
   float eps, lr, wd, exp_mult, step_mult, b3d, b3m;
+  float bm[3], am[3], bv, av;       // decays beta_1..3, beta_4 and 1 - beta (UPDATE_STATE: the accumulators move in this pass)
 };
 
 // Features of one round, normalized, split and packed: after the lane-half swap registers 0..3 are the B
@@ -148,6 +149,44 @@ struct Consts {
 struct Feat { unsigned ph[8], pl[8]; float p_old; };
 
 struct FeatTmp { float rs; };
+
+// A wave-uniform global pointer, held in scalar registers.
+__device__ __forceinline__ gc8 uniform_ptr(gc8 p) {
+  const unsigned long long a = (unsigned long long)p;
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)a), hi = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32));
+  return (gc8)(((unsigned long long)hi << 32) | lo);
+}
+
+// Stores go out as raw buffer stores whose descriptor starts at the round's (wave-uniform) row address: a lane that
+// must not store passes an offset beyond the descriptor's range and the hardware drops its write. No branch and no
+// change of the execution mask surrounds the store, so the compiler counts the memory operations in flight exactly
+// (with a skipped region it has to assume the fewest, and every wait for a load then also waits for the stores issued
+// before it to be acknowledged). Lane offsets of real elements stay below kStoreRange (the launcher's shape check).
+constexpr unsigned kStoreRange = 0xFFFFFE00u;
+constexpr unsigned kNoStore = 0xFFFFFFFFu;
+__device__ __forceinline__ void store_stream(float v, gc8 row_base, unsigned voff_or_none) {
+  const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void*)uniform_ptr(row_base), 0, (int)kStoreRange,
+                                                                      0x00020000);   // raw buffer, 32-bit data
+  __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rs, (int)voff_or_none, 0, 2 /* nontemporal */);
+}
+
+// UPDATE_STATE: the momentum and second-moment accumulators of this round's elements are updated HERE, from the
+// values of the previous step, in the same arithmetic as the statistics pass (which then only reads them), and stored:
+// M_i <- beta_i M_i + (1 - beta_i) g, V <- beta_4 V + (1 - beta_4) g^2. The features below are built from the new values.
+// `keep`: this lane's element lies inside the tile (the run-out rounds and the padding lanes compute, but store nothing).
+__device__ __forceinline__ void update_state(const Consts& C, Elem& e, const Streams& S, size_t rowoff, unsigned voff_bytes,
+                                             bool keep) {
+  const float g = e.g;
+  e.m1 = __builtin_fmaf(C.bm[0], e.m1, C.am[0] * g);   // the statistics pass's operations, in its order
+  e.m2 = __builtin_fmaf(C.bm[1], e.m2, C.am[1] * g);
+  e.m3 = __builtin_fmaf(C.bm[2], e.m3, C.am[2] * g);
+  e.v = __builtin_fmaf(C.bv, e.v, C.av * (g * g));
+  const unsigned vo = keep ? voff_bytes : kNoStore;
+  store_stream(e.m1, (gc8)((gf32)S.m1 + rowoff), vo);
+  store_stream(e.m2, (gc8)((gf32)S.m2 + rowoff), vo);
+  store_stream(e.m3, (gc8)((gf32)S.m3 + rowoff), vo);
+  store_stream(e.v, (gc8)((gf32)S.v + rowoff), vo);
+}
 
 // The feature computation in six slices (one per MFMA of the phase it hides behind). The products of the row and
 // column factors are formed in the slice that uses them (fewer values live across slices).
@@ -192,7 +231,7 @@ __device__ __forceinline__ void layer3_piece(const float4& w, const f32x16& h2a,
 
 }  // namespace
 
-template <bool RAW_RSQ>
+template <bool RAW_RSQ, bool UPDATE_STATE>
 __global__ void __launch_bounds__(kBlock, 2) k_apply_f16s(const TensorDev* __restrict__ tensors,
                                                           const ApplyTileDev* __restrict__ atiles, int n_atiles,
                                                           int* __restrict__ next_tile, float* __restrict__ ws,
@@ -211,6 +250,9 @@ __global__ void __launch_bounds__(kBlock, 2) k_apply_f16s(const TensorDev* __res
   }
   Consts C;
   C.eps = A.eps_acc; C.lr = A.lr; C.wd = A.wd; C.exp_mult = A.exp_mult; C.step_mult = A.step_mult;
+#pragma unroll
+  for (int i = 0; i < 3; ++i) { C.bm[i] = A.mom_decay[i]; C.am[i] = 1.0f - A.mom_decay[i]; }
+  C.bv = A.rms_decay; C.av = 1.0f - A.rms_decay;
   C.b3d = tail[kH * kH + kH + 2 * kH]; C.b3m = tail[kH * kH + kH + 2 * kH + 1];
   // ---- weights of this lane, split and packed in the order the accumulator layout asks for
   {
@@ -328,10 +370,12 @@ __global__ void __launch_bounds__(kBlock, 2) k_apply_f16s(const TensorDev* __res
   S.m1 = (gcf32)T.st; S.m2 = S.m1 + T.padN; S.m3 = S.m2 + T.padN; S.v = S.m3 + T.padN;
   const gf32 pout = (gf32)T.p;
   // lane offsets in bytes, relative to the tile's first column (which goes into the wave-uniform row offset): at most
-  // 4 (127 + n) with n < 2^30 whenever a tensor has a second row, so 32 bits hold them for every legal shape
+  // 4 (127 + n) <= kStoreRange - 4 whenever a tensor has a second row (the launcher sends wider ones to another kernel)
   const size_t c0 = (size_t)at.c0;
   const unsigned colc_ = 4u * (unsigned)((col_ok ? col : n - 1) - at.c0);
   const unsigned voff_pair = colc_ + (half ? 4u * (unsigned)n : 0u);
+  // wave-uniform element offset of round q's first row (the tile's first column included); only used for rows inside the tile
+  auto rowoff_of = [&](int q) __attribute__((always_inline)) { return (size_t)q * (size_t)n + c0; };
   // the pipeline's run-out rounds (q >= r1) read the tile's last row once more: a cache hit, not HBM traffic
   auto fetch = [&](int q) __attribute__((always_inline)) {
     const bool in_tile = q < r1;
@@ -396,9 +440,8 @@ __global__ void __launch_bounds__(kBlock, 2) k_apply_f16s(const TensorDev* __res
       swap32x2(da, db, ma, mb);
       const float d = (da + db) + C.b3d, mg = (ma + mb) + C.b3m;
       const float delta = d * __expf(mg * C.exp_mult) * C.step_mult;
-      if (col_ok && qe + half < r1)
-        __builtin_nontemporal_store(p_e - C.lr * (delta + C.wd * p_e),
-                                    (gf32)((gc8)(pout + ((size_t)qe * (size_t)n + c0)) + voff_pair));
+      store_stream(p_e - C.lr * (delta + C.wd * p_e), (gc8)(pout + ((size_t)qe * (size_t)n + c0)),
+                   col_ok && qe + half < r1 ? voff_pair : kNoStore);
     }
     p_e = p_n;
     LOPT_SB();
@@ -439,6 +482,7 @@ __global__ void __launch_bounds__(kBlock, 2) k_apply_f16s(const TensorDev* __res
     FeatTmp t;
     h2b = mfma(C.a2l[0], pk8(bh[0], bh[1], bh[2], bh[3]), C.cb2);
     LOPT_SB();
+    if (UPDATE_STATE) update_state(C, e, S, rowoff_of(qf), voff_pair, col_ok && qf + half < r1);
     feat_piece<0, RAW_RSQ>(C, e, rr4, t, f);
     LOPT_SB();
     h2b = mfma(C.a2h[0], pk8(bl[0], bl[1], bl[2], bl[3]), h2b);
@@ -472,6 +516,7 @@ __global__ void __launch_bounds__(kBlock, 2) k_apply_f16s(const TensorDev* __res
   {
     const float4 rr4 = L.rowrs[half];
     FeatTmp t;
+    if (UPDATE_STATE) update_state(C, es[0], S, rowoff_of(r0), voff_pair, col_ok && r0 + half < r1);
     feat_piece<0, RAW_RSQ>(C, es[0], rr4, t, f);
     feat_piece<1, RAW_RSQ>(C, es[0], rr4, t, f);
     feat_piece<2, RAW_RSQ>(C, es[0], rr4, t, f);
@@ -490,17 +535,22 @@ __global__ void __launch_bounds__(kBlock, 2) k_apply_f16s(const TensorDev* __res
 }
 
 // L.apply_counter must be zero when the kernel starts (k_finalize of the same sub-list clears it).
-void launch_apply_f16s(const Launch& L, const StepArgs& A, const WeightsDev& W, hipStream_t s) {
+// update_state: the statistics pass left M_1..3 and V as they were (launch_accum_stats with write_state = false) and this
+// pass moves them.
+void launch_apply_f16s(const Launch& L, const StepArgs& A, const WeightsDev& W, bool update_state, hipStream_t s) {
   if (L.n_atiles == 0) return;
   const int grid = L.n_atiles < L.resident_wgs ? L.n_atiles : L.resident_wgs;
   // v_rsq_f32 treats inputs below the smallest normal float as zero; with eps_acc that small the kernel
   // takes the library reciprocal square root (which rescales such inputs) instead of the bare instruction
-  if (A.eps_acc >= 1e-30f)
-    hipLaunchKernelGGL(k_apply_f16s<true>, dim3(grid), dim3(kBlock), 0, s, L.tensors, L.atiles, L.n_atiles,
-                       L.apply_counter, L.ws, A, W.mlp_tail);
-  else
-    hipLaunchKernelGGL(k_apply_f16s<false>, dim3(grid), dim3(kBlock), 0, s, L.tensors, L.atiles, L.n_atiles,
-                       L.apply_counter, L.ws, A, W.mlp_tail);
+  const bool raw = A.eps_acc >= 1e-30f;
+#define LOPT_LAUNCH_F16S(R, U)                                                                                  \
+  hipLaunchKernelGGL((k_apply_f16s<R, U>), dim3(grid), dim3(kBlock), 0, s, L.tensors, L.atiles, L.n_atiles,       \
+                     L.apply_counter, L.ws, A, W.mlp_tail)
+  if (raw && update_state) LOPT_LAUNCH_F16S(true, true);
+  else if (raw) LOPT_LAUNCH_F16S(true, false);
+  else if (update_state) LOPT_LAUNCH_F16S(false, true);
+  else LOPT_LAUNCH_F16S(false, false);
+#undef LOPT_LAUNCH_F16S
 }
 
 }  // namespace lopt

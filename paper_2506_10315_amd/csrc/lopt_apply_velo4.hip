@@ -13,6 +13,9 @@
 #ifndef LOPT_V4_STORE
 #define LOPT_V4_STORE store4s
 #endif
+#ifndef LOPT_V4_STATE_STORE
+#define LOPT_V4_STATE_STORE store4s
+#endif
 
 namespace lopt {
 
@@ -31,7 +34,9 @@ __device__ __forceinline__ float relu1(float x) {
   return __builtin_bit_cast(float, i > 0 ? i : 0);
 }
 
-template <bool VEC, bool RAW_RSQ>
+// UPDATE_STATE: the statistics pass left M_1..3 and V as they were; this pass forms the new values (the statistics
+// pass's operations, in its order: the same bits), builds the features from them and writes them back.
+template <bool VEC, bool RAW_RSQ, bool UPDATE_STATE>
 __device__ __forceinline__ void apply_velo4_tile(const TensorDev& T, const TileDev& tile, const float* __restrict__ ws,
                                                  const StepArgs& A) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -81,12 +86,14 @@ __device__ __forceinline__ void apply_velo4_tile(const TensorDev& T, const TileD
       }
     }
   }
-  const float* __restrict__ M1 = T.st;
-  const float* __restrict__ M2 = T.st + (size_t)T.padN;
-  const float* __restrict__ M3 = T.st + 2 * (size_t)T.padN;
-  const float* __restrict__ Vp = T.st + 3 * (size_t)T.padN;
+  float* __restrict__ M1 = T.st;
+  float* __restrict__ M2 = T.st + (size_t)T.padN;
+  float* __restrict__ M3 = T.st + 2 * (size_t)T.padN;
+  float* __restrict__ Vp = T.st + 3 * (size_t)T.padN;
   const float* rst = T.st + 4 * (size_t)T.padN;
   const float eps = A.eps_acc, lr = A.lr, wd = A.wd;
+  const float bm1 = A.mom_decay[0], bm2 = A.mom_decay[1], bm3 = A.mom_decay[2], bv = A.rms_decay;
+  const float am1 = 1.0f - bm1, am2 = 1.0f - bm2, am3 = 1.0f - bm3, av = 1.0f - bv;
 
   for (int r = r0 + wave; r < r1; r += 4) {
     const size_t ro = (size_t)r * n;
@@ -116,10 +123,18 @@ __device__ __forceinline__ void apply_velo4_tile(const TensorDev& T, const TileD
     }
     float x[4][kVE];
     f32x4 h[4];
+    float n1[4], n2[4], n3[4], nv[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const float g = get(g4, e);
-      const float q1 = get(m1, e), q2 = get(m2, e), q3 = get(m3, e), v = get(v4, e);
+      float q1 = get(m1, e), q2 = get(m2, e), q3 = get(m3, e), v = get(v4, e);
+      if (UPDATE_STATE) {
+        q1 = __builtin_fmaf(bm1, q1, am1 * g);
+        q2 = __builtin_fmaf(bm2, q2, am2 * g);
+        q3 = __builtin_fmaf(bm3, q3, am3 * g);
+        v = __builtin_fmaf(bv, v, av * (g * g));
+        n1[e] = q1; n2[e] = q2; n3[e] = q3; nv[e] = v;
+      }
       const float rs = RAW_RSQ ? __builtin_amdgcn_rsqf(v + eps) : rsqrtf(v + eps);
       const float f0 = rr[0] * get(rc[0], e), f1 = rr[1] * get(rc[1], e), f2 = rr[2] * get(rc[2], e);
       x[e][0] = g; x[e][1] = get(p4, e); x[e][2] = q1; x[e][3] = q2; x[e][4] = q3; x[e][5] = v;
@@ -128,6 +143,12 @@ __device__ __forceinline__ void apply_velo4_tile(const TensorDev& T, const TileD
       x[e][13] = q1 * f0; x[e][14] = q2 * f1; x[e][15] = q3 * f2;
       x[e][16] = fminf(fmaxf(g, -0.1f), 0.1f);
       h[e] = rowv + colv[e];
+    }
+    if (UPDATE_STATE) {   // stored while the values are live as features anyway
+      LOPT_V4_STATE_STORE<VEC>(M1 + ro, col, n, make_float4(n1[0], n1[1], n1[2], n1[3]));
+      LOPT_V4_STATE_STORE<VEC>(M2 + ro, col, n, make_float4(n2[0], n2[1], n2[2], n2[3]));
+      LOPT_V4_STATE_STORE<VEC>(M3 + ro, col, n, make_float4(n3[0], n3[1], n3[2], n3[3]));
+      LOPT_V4_STATE_STORE<VEC>(Vp + ro, col, n, make_float4(nv[0], nv[1], nv[2], nv[3]));
     }
     // layer 1: the four elements of the lane are four independent accumulation chains
 #pragma unroll
@@ -162,26 +183,30 @@ __device__ __forceinline__ void apply_velo4_tile(const TensorDev& T, const TileD
   }
 }
 
-template <bool RAW_RSQ>
+template <bool RAW_RSQ, bool UPDATE_STATE>
 __global__ void __launch_bounds__(kBlock, 4) k_apply_velo4(const TensorDev* __restrict__ tensors,
                                                         const TileDev* __restrict__ tiles, float* __restrict__ ws,
                                                         StepArgs A) {
   const TileDev tile = tiles[blockIdx.x];
   const TensorDev& T = tensors[tile.tensor];
-  if (T.vec) apply_velo4_tile<true, RAW_RSQ>(T, tile, ws, A);
-  else apply_velo4_tile<false, RAW_RSQ>(T, tile, ws, A);
+  if (T.vec) apply_velo4_tile<true, RAW_RSQ, UPDATE_STATE>(T, tile, ws, A);
+  else apply_velo4_tile<false, RAW_RSQ, UPDATE_STATE>(T, tile, ws, A);
 }
 
 bool apply_velo4_available(const StepArgs& A) { return A.kind == LOPT_VELO && A.H == kVH && A.HP == kVH; }
 
-void launch_apply_velo4(const Launch& L, const StepArgs& A, hipStream_t s) {
+void launch_apply_velo4(const Launch& L, const StepArgs& A, bool update_state, hipStream_t s) {
   if (L.n_tiles == 0) return;
   // v_rsq_f32 treats inputs below the smallest normal float as zero; with eps_acc that small the kernel takes the
   // library reciprocal square root (which rescales such inputs) instead of the bare instruction
-  if (A.eps_acc >= 1e-30f)
-    hipLaunchKernelGGL(k_apply_velo4<true>, dim3(L.n_tiles), dim3(kBlock), 0, s, L.tensors, L.tiles, L.ws, A);
-  else
-    hipLaunchKernelGGL(k_apply_velo4<false>, dim3(L.n_tiles), dim3(kBlock), 0, s, L.tensors, L.tiles, L.ws, A);
+  const bool raw = A.eps_acc >= 1e-30f;
+#define LOPT_LAUNCH_V4(R, U) \
+  hipLaunchKernelGGL((k_apply_velo4<R, U>), dim3(L.n_tiles), dim3(kBlock), 0, s, L.tensors, L.tiles, L.ws, A)
+  if (raw && update_state) LOPT_LAUNCH_V4(true, true);
+  else if (raw) LOPT_LAUNCH_V4(true, false);
+  else if (update_state) LOPT_LAUNCH_V4(false, true);
+  else LOPT_LAUNCH_V4(false, false);
+#undef LOPT_LAUNCH_V4
 }
 
 }  // namespace lopt

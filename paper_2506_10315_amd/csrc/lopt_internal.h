@@ -100,7 +100,8 @@ void launch_fill_zero(const Launch&, const StepArgs&, hipStream_t);
 // come before any tensor's LSTM state is rewritten
 void launch_rowcol_sums(const Launch&, const StepArgs&, const WeightsDev&, float* hbar_part, float* b_eff, hipStream_t);
 void launch_rc_update(const Launch&, const StepArgs&, const WeightsDev&, float* hbar_part, float* b_eff, hipStream_t);
-void launch_accum_stats(const Launch&, const StepArgs&, hipStream_t);
+// write_state = false: M_1..3 and V stay as they are (the strip-form apply pass updates them, see launch_apply_f16s)
+void launch_accum_stats(const Launch&, const StepArgs&, bool write_state, hipStream_t);
 void launch_finalize(const Launch&, const StepArgs&, const WeightsDev&, float* lstm_u, hipStream_t);
 void launch_velo_lstm(const Launch&, const StepArgs&, const WeightsDev&, const float* lstm_u, const float* b_eff,
                       float* h_new, hipStream_t);
@@ -111,7 +112,7 @@ void launch_apply_velo(const Launch&, const StepArgs&, const WeightsDev&, hipStr
 bool apply_mfma_available(const StepArgs&);
 void launch_apply_mfma(const Launch&, const StepArgs&, const WeightsDev&, hipStream_t);
 bool apply_velo4_available(const StepArgs&);
-void launch_apply_velo4(const Launch&, const StepArgs&, hipStream_t);
-void launch_apply_f16s(const Launch&, const StepArgs&, const WeightsDev&, hipStream_t);
+void launch_apply_velo4(const Launch&, const StepArgs&, bool update_state, hipStream_t);
+void launch_apply_f16s(const Launch&, const StepArgs&, const WeightsDev&, bool update_state, hipStream_t);
 
 }  // namespace lopt

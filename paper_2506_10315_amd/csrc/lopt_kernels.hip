@@ -340,77 +340,65 @@ void launch_rc_update(const Launch& L, const StepArgs& A, const WeightsDev& W, f
 // factor sqrt(mean(r_k)+eps) of the factored features is applied per tensor in k_finalize.
 // Streaming accesses of this pass: nontemporal loads, ordinary stores (measured: 0.649 ms on the ViT-B/16 set
 // against 0.670 plain/plain, 0.670 plain/nontemporal, 0.680 nontemporal/nontemporal).
-#ifndef LOPT_ACC_LOAD
-#define LOPT_ACC_LOAD load4s
-#endif
-#ifndef LOPT_ACC_STORE
-#define LOPT_ACC_STORE store4
-#endif
-template <bool VEC>
+// Rows that are not 16-byte aligned (n % 4 != 0; a small share of any list): one column per lane and sweep, four
+// sweeps of 64 columns over the tile, every access a coalesced dword. Kept small in registers on purpose: the
+// kernel's register count is the larger of its two paths, and it decides how many of its workgroups fit beside the
+// apply kernel of another tensor group.
+template <bool WRITE>
 __device__ __forceinline__ void accum_tile(const TensorDev& T, const TileDev& tile, float* __restrict__ ws,
                                            const StepArgs& A, float (&acc)[kNStat]) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = T.n, m = T.m;
-  const int col = tile.tj * kTileCols + 4 * lane;
   const int r0 = tile.ti * T.TR;
   const int r1 = min(r0 + T.TR, m);
-  float4 rc[3];
-#pragma unroll
-  for (int k = 0; k < 3; ++k) rc[k] = load4<VEC>(ws + T.oRC + (size_t)k * T.padn, col, n);
-  float* __restrict__ M1 = T.st;
-  float* __restrict__ M2 = T.st + (size_t)T.padN;
-  float* __restrict__ M3 = T.st + 2 * (size_t)T.padN;
-  float* __restrict__ Vp = T.st + 3 * (size_t)T.padN;
+  const size_t pN = T.padN;
   const float b1 = A.mom_decay[0], b2 = A.mom_decay[1], b3 = A.mom_decay[2], b4 = A.rms_decay;
   const float eps = A.eps_acc;
-  for (int r = r0 + wave; r < r1; r += 4) {
-    const size_t ro = (size_t)r * n;
-    const float4 g4 = LOPT_ACC_LOAD<VEC>(T.g + ro, col, n);
-    const float4 p4 = LOPT_ACC_LOAD<VEC>(T.p + ro, col, n);
-    const float4 m1 = LOPT_ACC_LOAD<VEC>(M1 + ro, col, n);
-    const float4 m2 = LOPT_ACC_LOAD<VEC>(M2 + ro, col, n);
-    const float4 m3 = LOPT_ACC_LOAD<VEC>(M3 + ro, col, n);
-    const float4 v4 = LOPT_ACC_LOAD<VEC>(Vp + ro, col, n);
-    float rr[3];
+#pragma unroll 1
+  for (int sweep = 0; sweep < kTileCols / kWave; ++sweep) {
+    const int c = tile.tj * kTileCols + sweep * kWave + lane;
+    if (c >= n) break;   // columns only grow with the sweep
+    float rc[3];
 #pragma unroll
-    for (int k = 0; k < 3; ++k) rr[k] = ws[T.oRR + (size_t)k * T.padm + r];
-    float o1[4], o2[4], o3[4], ov[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const float g = get(g4, e), p = get(p4, e);
-      const float nm1 = b1 * get(m1, e) + (1.0f - b1) * g;
-      const float nm2 = b2 * get(m2, e) + (1.0f - b2) * g;
-      const float nm3 = b3 * get(m3, e) + (1.0f - b3) * g;
-      const float nv = b4 * get(v4, e) + (1.0f - b4) * (g * g);
-      o1[e] = nm1; o2[e] = nm2; o3[e] = nm3; ov[e] = nv;
-      if (col + e < n) {
-        const float rs = rsqrtf(nv + eps);
-        const float f0 = rr[0] * get(rc[0], e), f1 = rr[1] * get(rc[1], e), f2 = rr[2] * get(rc[2], e);
-        const float gc = fminf(fmaxf(g, -0.1f), 0.1f);
-        float t;
-        acc[0] += g * g;
-        acc[1] += p * p;
-        acc[2] += nm1 * nm1;
-        acc[3] += nm2 * nm2;
-        acc[4] += nm3 * nm3;
-        acc[5] += nv * nv;
-        t = nm1 * rs; acc[6] += t * t;
-        t = nm2 * rs; acc[7] += t * t;
-        t = nm3 * rs; acc[8] += t * t;
-        acc[9] += rs * rs;
-        t = g * f0; acc[10] += t * t;
-        t = g * f1; acc[11] += t * t;
-        t = g * f2; acc[12] += t * t;
-        t = nm1 * f0; acc[13] += t * t;
-        t = nm2 * f1; acc[14] += t * t;
-        t = nm3 * f2; acc[15] += t * t;
-        acc[16] += gc * gc;
+    for (int k = 0; k < 3; ++k) rc[k] = ws[T.oRC + (size_t)k * T.padn + c];
+#pragma unroll 1
+    for (int r = r0 + wave; r < r1; r += 4) {
+      const size_t ro = (size_t)r * n + c;
+      const float g = __builtin_nontemporal_load(T.g + ro), p = __builtin_nontemporal_load(T.p + ro);
+      // explicit fused multiply-adds: the apply pass may form the same values again (lopt_state_pass), bit for bit
+      const float nm1 = __builtin_fmaf(b1, __builtin_nontemporal_load(T.st + ro), (1.0f - b1) * g);
+      const float nm2 = __builtin_fmaf(b2, __builtin_nontemporal_load(T.st + pN + ro), (1.0f - b2) * g);
+      const float nm3 = __builtin_fmaf(b3, __builtin_nontemporal_load(T.st + 2 * pN + ro), (1.0f - b3) * g);
+      const float nv = __builtin_fmaf(b4, __builtin_nontemporal_load(T.st + 3 * pN + ro), (1.0f - b4) * (g * g));
+      const float rs = rsqrtf(nv + eps);
+      const float f0 = ws[T.oRR + r] * rc[0], f1 = ws[T.oRR + (size_t)T.padm + r] * rc[1];
+      const float f2 = ws[T.oRR + 2 * (size_t)T.padm + r] * rc[2];
+      const float gc = fminf(fmaxf(g, -0.1f), 0.1f);
+      float t;
+      acc[0] += g * g;
+      acc[1] += p * p;
+      acc[2] += nm1 * nm1;
+      acc[3] += nm2 * nm2;
+      acc[4] += nm3 * nm3;
+      acc[5] += nv * nv;
+      t = nm1 * rs; acc[6] += t * t;
+      t = nm2 * rs; acc[7] += t * t;
+      t = nm3 * rs; acc[8] += t * t;
+      acc[9] += rs * rs;
+      t = g * f0; acc[10] += t * t;
+      t = g * f1; acc[11] += t * t;
+      t = g * f2; acc[12] += t * t;
+      t = nm1 * f0; acc[13] += t * t;
+      t = nm2 * f1; acc[14] += t * t;
+      t = nm3 * f2; acc[15] += t * t;
+      acc[16] += gc * gc;
+      if (WRITE) {
+        T.st[ro] = nm1;
+        T.st[pN + ro] = nm2;
+        T.st[2 * pN + ro] = nm3;
+        T.st[3 * pN + ro] = nv;
       }
     }
-    LOPT_ACC_STORE<VEC>(M1 + ro, col, n, make_float4(o1[0], o1[1], o1[2], o1[3]));
-    LOPT_ACC_STORE<VEC>(M2 + ro, col, n, make_float4(o2[0], o2[1], o2[2], o2[3]));
-    LOPT_ACC_STORE<VEC>(M3 + ro, col, n, make_float4(o3[0], o3[1], o3[2], o3[3]));
-    LOPT_ACC_STORE<VEC>(Vp + ro, col, n, make_float4(ov[0], ov[1], ov[2], ov[3]));
   }
 }
 
@@ -424,7 +412,7 @@ typedef float __attribute__((ext_vector_type(4))) f32x4v;
 typedef const f32x4v __attribute__((address_space(1)))* gcv4;
 typedef f32x4v __attribute__((address_space(1)))* gv4;
 
-template <bool RAW_RCP>
+template <bool RAW_RCP, bool WRITE>
 __device__ __forceinline__ void accum_tile_vec(const TensorDev& T, const TileDev& tile, float* __restrict__ ws,
                                                const StepArgs& A, float (&acc)[kNStat]) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -463,10 +451,11 @@ __device__ __forceinline__ void accum_tile_vec(const TensorDev& T, const TileDev
     for (int e = 0; e < 4; ++e) {
       const float g = g4[e], p = p4[e];
       const float g2 = g * g;
-      const float nm1 = b1 * m1[e] + a1 * g;
-      const float nm2 = b2 * m2[e] + a2 * g;
-      const float nm3 = b3 * m3[e] + a3 * g;
-      const float nv = b4 * v4[e] + a4 * g2;
+      // explicit fused multiply-adds: the apply pass may form the same values again (lopt_state_pass), bit for bit
+      const float nm1 = __builtin_fmaf(b1, m1[e], a1 * g);
+      const float nm2 = __builtin_fmaf(b2, m2[e], a2 * g);
+      const float nm3 = __builtin_fmaf(b3, m3[e], a3 * g);
+      const float nv = __builtin_fmaf(b4, v4[e], a4 * g2);
       o1[e] = nm1; o2[e] = nm2; o3[e] = nm3; ov[e] = nv;
       const float s1 = nm1 * nm1, s2 = nm2 * nm2, s3 = nm3 * nm3;
       const float rs2 = RAW_RCP ? __builtin_amdgcn_rcpf(nv + eps) : 1.0f / (nv + eps);
@@ -481,14 +470,19 @@ __device__ __forceinline__ void accum_tile_vec(const TensorDev& T, const TileDev
       acc[13] += s1 * f0; acc[14] += s2 * f1; acc[15] += s3 * f2;
       acc[16] += fminf(g2, clip2);
     }
-    *(gv4)(T.st + ro) = o1;
-    *(gv4)(T.st + pN + ro) = o2;
-    *(gv4)(T.st + 2 * pN + ro) = o3;
-    *(gv4)(T.st + 3 * pN + ro) = ov;
+    if (WRITE) {
+      *(gv4)(T.st + ro) = o1;
+      *(gv4)(T.st + pN + ro) = o2;
+      *(gv4)(T.st + 2 * pN + ro) = o3;
+      *(gv4)(T.st + 3 * pN + ro) = ov;
+    }
   }
 }
 
-template <bool RAW_RCP>
+// WRITE = false: the accumulators are only read (their new values are formed for the statistics and dropped); the apply
+// pass of the same step updates them in memory (strip-form apply kernel of small_fc_lopt, which has HBM bandwidth to
+// spare: 16 of this pass's 40 bytes per element move there).
+template <bool RAW_RCP, bool WRITE>
 __global__ void __launch_bounds__(kBlock) k_accum_stats(const TensorDev* __restrict__ tensors,
                                                         const TileDev* __restrict__ tiles, float* __restrict__ ws,
                                                         StepArgs A) {
@@ -498,18 +492,22 @@ __global__ void __launch_bounds__(kBlock) k_accum_stats(const TensorDev* __restr
   float acc[kNStat];
 #pragma unroll
   for (int q = 0; q < kNStat; ++q) acc[q] = 0.f;
-  if (T.vec) accum_tile_vec<RAW_RCP>(T, tile, ws, A, acc);
-  else accum_tile<false>(T, tile, ws, A, acc);
+  if (T.vec) accum_tile_vec<RAW_RCP, WRITE>(T, tile, ws, A, acc);
+  else accum_tile<WRITE>(T, tile, ws, A, acc);
   const int lt = tile.ti * T.nct + tile.tj;
   block_sum<kNStat>(acc, red, ws + T.oStatPart + (size_t)lt * kStatStride);
 }
 
-void launch_accum_stats(const Launch& L, const StepArgs& A, hipStream_t s) {
+void launch_accum_stats(const Launch& L, const StepArgs& A, bool write_state, hipStream_t s) {
   if (L.n_tiles == 0) return;
-  if (A.eps_acc >= 1e-30f)
-    hipLaunchKernelGGL(k_accum_stats<true>, dim3(L.n_tiles), dim3(kBlock), 0, s, L.tensors, L.tiles, L.ws, A);
-  else
-    hipLaunchKernelGGL(k_accum_stats<false>, dim3(L.n_tiles), dim3(kBlock), 0, s, L.tensors, L.tiles, L.ws, A);
+  const bool raw = A.eps_acc >= 1e-30f;
+#define LOPT_LAUNCH_ACC(R, Wr) \
+  hipLaunchKernelGGL((k_accum_stats<R, Wr>), dim3(L.n_tiles), dim3(kBlock), 0, s, L.tensors, L.tiles, L.ws, A)
+  if (raw && write_state) LOPT_LAUNCH_ACC(true, true);
+  else if (raw) LOPT_LAUNCH_ACC(true, false);
+  else if (write_state) LOPT_LAUNCH_ACC(false, true);
+  else LOPT_LAUNCH_ACC(false, false);
+#undef LOPT_LAUNCH_ACC
 }
 
 // ----------------------------------------------------------------------------- finalize

@@ -63,12 +63,14 @@ def oracle_config_from(cfg) -> O.OracleConfig:
         lstm_hidden=int(cfg.lstm_hidden), n_bank=int(cfg.n_bank))
 
 
-def make_cfg(kind: str, hidden=None, lstm_hidden=None, n_bank=None, apply_kernel=None, groups=None):
+def make_cfg(kind: str, hidden=None, lstm_hidden=None, n_bank=None, apply_kernel=None, groups=None, state_pass=None):
     import paper_2506_10315_amd as P
-    from paper_2506_10315_amd.binding import APPLY_KERNELS
+    from paper_2506_10315_amd.binding import APPLY_KERNELS, STATE_PASSES
     cfg = P.default_config(P.LOPT_SMALL_FC if kind == "small_fc_lopt" else P.LOPT_VELO)
     if apply_kernel is not None:
         cfg.apply_kernel = APPLY_KERNELS[apply_kernel]
+    if state_pass is not None:
+        cfg.state_pass = STATE_PASSES[state_pass]
     if groups is not None:
         cfg.groups = groups
     if hidden is not None:

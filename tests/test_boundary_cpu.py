@@ -126,6 +126,12 @@ def test_create_refuses_unknown_tuning_knob_values_and_non_finite_weights(monkey
     c.groups = 17
     assert L.lopt_create(C.byref(c), wp, 2402, C.byref(ctx)) == 1 and b"groups" in L.lopt_last_error(None)
     c = P.default_config(0)
+    c.state_pass = 3
+    assert L.lopt_create(C.byref(c), wp, 2402, C.byref(ctx)) == 1 and b"state_pass" in L.lopt_last_error(None)
+    c = P.default_config(0)
+    monkeypatch.setenv("LOPT_STATE_PASS", "1")              # names only: auto, stats, apply
+    assert L.lopt_create(C.byref(c), wp, 2402, C.byref(ctx)) == 1 and b"LOPT_STATE_PASS" in L.lopt_last_error(None)
+    monkeypatch.delenv("LOPT_STATE_PASS")
     monkeypatch.setenv("LOPT_APPLY", "mfma_f16")            # a misspelt variant must not silently mean "auto"
     assert L.lopt_create(C.byref(c), wp, 2402, C.byref(ctx)) == 1 and b"LOPT_APPLY" in L.lopt_last_error(None)
     monkeypatch.delenv("LOPT_APPLY")

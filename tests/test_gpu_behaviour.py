@@ -72,6 +72,36 @@ def test_groups_field_of_the_configuration_selects_the_plan_per_context():
         assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
 
 
+@pytest.mark.parametrize("kind,groups", [("small_fc_lopt", 1), ("small_fc_lopt", 3), ("velo", 1)])
+def test_state_pass_field_moves_the_accumulator_update_without_changing_a_bit(kind, groups):
+    # The new M_1..3 and V are written either by the statistics pass or by the default apply kernels (split-fp16 strip
+    # kernel of small_fc_lopt, width-4 kernel of VeLO), which then form them a second time with the same fp32
+    # operations: parameters AND every word of the state must agree bit for bit, ragged and unaligned shapes included,
+    # with and without the tensor-group pipeline.
+    import torch
+    import paper_2506_10315_amd as P
+    shapes = SHAPES + [(300, 257), (2, 1000), (1, 77), (129, 64)]
+    outs = []
+    for state_pass in ("stats", "apply"):
+        if kind == "small_fc_lopt":
+            cfg = Hn.make_cfg(kind, groups=groups, state_pass=state_pass)
+        else:
+            cfg = Hn.make_cfg(kind, lstm_hidden=32, n_bank=8, state_pass=state_pass)
+        w = Hn.random_weights(cfg, 0)
+        specs = [W.TensorSpec(f"t{i}", s) for i, s in enumerate(shapes)]
+        case = Hn.Case(202, specs, "gauss_logscale")
+        opt = P.LearnedOptimizer(cfg, w, shapes)
+        p = [torch.from_numpy(case.p0(i)).to("cuda:0") for i in range(len(specs))]
+        for t in range(4):
+            g = [torch.from_numpy(case.grad(i, t)).to("cuda:0") for i in range(len(specs))]
+            opt.step(p, g, lr=0.7, weight_decay=0.01, step=t, loss=1.5 - 0.1 * t)
+        torch.cuda.synchronize()
+        outs.append([x.cpu().numpy().copy() for x in p] + [x.cpu().numpy().copy() for x in opt.state])
+        opt.close()
+    for x, y in zip(*outs):
+        assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
+
+
 @pytest.mark.parametrize("groups", [2, 3, 16])
 def test_group_pipeline_is_bit_identical_to_one_stream(groups, monkeypatch):
     # LOPT_GROUPS (read when the context is created) cuts the list into tensor groups whose HBM-bound passes run on

@@ -54,9 +54,11 @@ def test_velo_long_list_takes_the_batched_hypernetwork_head(hidden, lstm_hidden,
     assert worst["param"] <= Hn.TOL_PARAM
 
 
-def test_velo_config1_shapes_free_running_with_clip_active():
-    # gradients of order 0.1 so that the clipped-gradient feature differs from the gradient
-    cfg = Hn.make_cfg("velo")
+@pytest.mark.parametrize("state_pass", ["apply", "stats"])
+def test_velo_config1_shapes_free_running_with_clip_active(state_pass):
+    # gradients of order 0.1 so that the clipped-gradient feature differs from the gradient; the width-4 apply kernel
+    # with the accumulator update in either pass
+    cfg = Hn.make_cfg("velo", state_pass=state_pass)
     w = W.velo_weights(0)
 
     class BigGrad(Hn.Case):
@@ -101,11 +103,12 @@ def test_random_shape_lists(kind, seed):
                 lr_fn=lambda t: 0.5, wd=0.01)
 
 
-@pytest.mark.parametrize("variant", ["valu", "mfma_f32", "mfma_f16s"])
-def test_every_apply_kernel_variant_matches_the_oracle(variant):
+@pytest.mark.parametrize("variant,state_pass", [("valu", None), ("mfma_f32", None), ("mfma_f16s", "apply"),
+                                                ("mfma_f16s", "stats")])
+def test_every_apply_kernel_variant_matches_the_oracle(variant, state_pass):
     # the configuration's apply_kernel field selects the apply kernel for hidden width 32: vector ALU, fp32 MFMA, or
-    # split-fp16 MFMA (the default). All three must meet the same bar.
-    cfg = Hn.make_cfg("small_fc_lopt", apply_kernel=variant)
+    # split-fp16 MFMA (the default), the last with the accumulator update in either pass. All must meet the same bar.
+    cfg = Hn.make_cfg("small_fc_lopt", apply_kernel=variant, state_pass=state_pass)
     w = W.small_fc_weights(2, 32)
     shapes = [(256, 256), (256,), (64, 256), (300, 257), (33, 1000), (7,)]
     worst = Hn.run_free(Hn.Case(105, _specs(shapes), "student_t3"), cfg, w, 6, lr_fn=lambda t: 0.8, wd=0.01)
