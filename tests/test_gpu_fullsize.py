@@ -168,6 +168,12 @@ def test_widest_tensor_matches_its_periodic_base_pattern(capsys):
     _periodic_tensor_case("small_fc_lopt", 1, 1 << 26, _progress(capsys), "widest")
 
 
+def test_two_row_tensor_with_lane_offsets_beyond_2_to_31(capsys):
+    # 2 x 536,870,944: the upper half of every wavefront of the strip-form apply kernel addresses its row with a lane
+    # offset of 4 n = 2^31 + 128 bytes and more, in the loads and in the (range-checked, unsigned) buffer stores
+    _periodic_tensor_case("small_fc_lopt", 1, (1 << 27) + 8, _progress(capsys), "two rows, 2^29 + 32 columns", pr=2, pc=4)
+
+
 def test_tallest_tensor_matches_its_periodic_base_pattern(capsys):
     # 2^28 x 4: the tallest statistics tiles (64 row tiles of 4,194,304 rows), a million row blocks in the row/column
     # pass, apply tiles with one of four column strips in use
