@@ -33,7 +33,9 @@
 //     32-vector per row. The workgroup computes it once per tile into LDS as packed (hi, lo) fp16 pairs;
 //     it enters through ONE extra MFMA per tile: A carries (hi, lo) in k slots 0 and 1 of the row's lane
 //     half, B is the constant (1, 1) there and 0 elsewhere.
-//   * Loads are one dword per array, lane and round (a 128-byte line per row), issued kSets rounds ahead.
+//   * Loads are one dword per array, lane and round (a 128-byte line per row), issued kSets rounds ahead. Stores
+//     (the parameter, and with UPDATE_STATE the four accumulators) are raw buffer stores relative to the round's row
+//     address; lanes outside the tile are dropped by the descriptor's range check, not by a branch.
 //
 // Schedule. Measured on gfx950: the 16-bit MFMA costs a wavefront about two issue slots when
 // independent vector instructions of the SAME wavefront follow it in program order, and its full 32

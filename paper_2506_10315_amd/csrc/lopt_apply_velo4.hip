@@ -4,7 +4,7 @@
 // lanes. With A = W[k][i] (i = lane & 3, the same in every group) and B = feature k of the lane's OWN
 // element, lane l ends up with all four hidden pre-activations of its own element in the four
 // accumulator registers: no cross-lane traffic at all, exact fp32, and twice the FMA rate of the
-// vector ALU (which is what bounds this pass once the weights are per tensor and only 28 bytes per
+// vector ALU (which is what bounds this pass once the weights are per tensor and only 28 to 44 bytes per
 // element move). The 12 row/column-constant features enter through the C operand (4 values per row
 // and 4 per column), so layer 1 is 17 MFMAs per element instead of 29.
 #include "lopt_internal.h"

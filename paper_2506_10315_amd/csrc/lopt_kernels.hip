@@ -480,8 +480,8 @@ __device__ __forceinline__ void accum_tile_vec(const TensorDev& T, const TileDev
 }
 
 // WRITE = false: the accumulators are only read (their new values are formed for the statistics and dropped); the apply
-// pass of the same step updates them in memory (strip-form apply kernel of small_fc_lopt, which has HBM bandwidth to
-// spare: 16 of this pass's 40 bytes per element move there).
+// pass of the same step forms them again and writes them (the two default apply kernels can; a read-only stream
+// sustains a higher share of the HBM rate than a read-write one, and 16 of this pass's 40 bytes per element move there).
 template <bool RAW_RCP, bool WRITE>
 __global__ void __launch_bounds__(kBlock) k_accum_stats(const TensorDev* __restrict__ tensors,
                                                         const TileDev* __restrict__ tiles, float* __restrict__ ws,
