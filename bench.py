@@ -258,7 +258,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-also", action="store_true", help="default workload only: skip the `also` list")
     ap.add_argument("--micro", default=None,
-                    help="time a micro-workload instead of a numbered config: layer1000 or mlp_w<W>_d<D>")
+                    help="time a micro-workload instead of a numbered config: layer1000, layer8192 or mlp_w<W>_d<D>")
     ap.add_argument("--graph", action="store_true",
                     help="also time one step captured in a HIP graph (lopt_step_static) and replayed")
     ap.add_argument("--n-tiny", type=int, default=None,

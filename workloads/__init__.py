@@ -144,9 +144,12 @@ def mlp_shapes(width: int, depth: int, in_dim: int = 1024, out_dim: int = 10) ->
 
 def micro_workload(name: str, optimizer: str = "small_fc_lopt") -> Workload:
     """The paper's micro-workloads as shapes: 'layer1000' = one 1000x1000 weight without bias (its profiler
-    figure); 'mlp_w<W>_d<D>' = MLP of width W and depth D (its scaling figure)."""
+    figure); 'layer8192' = one 8192x8192 matrix (the step-time figure of its H100 appendix); 'mlp_w<W>_d<D>' = MLP of
+    width W and depth D (its scaling figure)."""
     if name == "layer1000":
         tensors = [TensorSpec("fc.weight", (1000, 1000))]
+    elif name == "layer8192":
+        tensors = [TensorSpec("fc.weight", (8192, 8192))]
     elif name.startswith("mlp_w"):
         w, d = name[5:].split("_d")
         tensors = mlp_shapes(int(w), int(d))
