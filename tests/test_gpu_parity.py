@@ -41,6 +41,18 @@ def test_velo_odd_shapes(hidden, lstm_hidden, n_bank):
     Hn.run_free(Hn.Case(102, _specs(ODD_SHAPES), "gauss_logscale"), cfg, w, 4, lr_fn=lambda t: 0.5, wd=0.01)
 
 
+@pytest.mark.parametrize("kind", ["small_fc_lopt", "velo"])
+def test_unaligned_rows_at_every_sweep_boundary(kind):
+    # rows that are not 16-byte aligned (n % 4 != 0) take the statistics pass one column per lane, 64 columns per sweep,
+    # four sweeps per 256-column tile: widths just below and above every sweep and tile boundary, heights below, at and
+    # above a tile's 64 rows (the apply kernels see the same widths through their ragged last strips)
+    cfg = Hn.make_cfg(kind) if kind == "small_fc_lopt" else Hn.make_cfg(kind, lstm_hidden=32, n_bank=8)
+    w = Hn.random_weights(cfg, seed=21)
+    shapes = [(9, 63), (70, 65), (64, 127), (3, 129), (130, 191), (65, 193), (11, 255), (66, 257), (5, 321), (2, 513)]
+    worst = Hn.run_free(Hn.Case(112, _specs(shapes), "gauss_logscale"), cfg, w, 3, lr_fn=lambda t: 0.5, wd=0.01)
+    assert worst["param"] <= Hn.TOL_PARAM
+
+
 @pytest.mark.parametrize("hidden,lstm_hidden,n_bank", [(3, 33, 5), (4, 512, 256)])
 def test_velo_long_list_takes_the_batched_hypernetwork_head(hidden, lstm_hidden, n_bank):
     # from 1024 tensors on the head of the hypernetwork runs as two batched matrix products and a scatter kernel
