@@ -340,6 +340,7 @@ void launch_rc_update(const Launch& L, const StepArgs& A, const WeightsDev& W, f
 // factor sqrt(mean(r_k)+eps) of the factored features is applied per tensor in k_finalize.
 // Streaming accesses of this pass: nontemporal loads, ordinary stores (measured: 0.649 ms on the ViT-B/16 set
 // against 0.670 plain/plain, 0.670 plain/nontemporal, 0.680 nontemporal/nontemporal).
+
 // Rows that are not 16-byte aligned (n % 4 != 0; a small share of any list): one column per lane and sweep, four
 // sweeps of 64 columns over the tile, every access a coalesced dword. Kept small in registers on purpose: the
 // kernel's register count is the larger of its two paths, and it decides how many of its workgroups fit beside the
